@@ -1,0 +1,304 @@
+// Block-sparse flash attention for gfx950 (appendix Alg. 4; Alg. 2 for the text rows; Eq. 1 inside
+// the visited blocks).
+//
+// One workgroup owns one query block of BLK rows of one (batch, head): BLK/32 wavefronts, each with
+// 32 query rows.  It walks the ascending list of selected key blocks.  Per key block:
+//     S^T = K Q^T         v_mfma_f32_32x32x16_bf16, K fragments from LDS, Q fragments in registers
+//     online softmax      float32, base-2 exponent, statistics per query row
+//     O^T += V^T P^T      v_mfma_f32_32x32x16_bf16, V^T fragments from LDS, P^T straight from the
+//                         S^T accumulators
+// Working on the transposed products keeps one query row in one lane (column) of every
+// accumulator, so the row maximum and row sum are lane-local (one cross-half exchange), and the
+// accumulator layout of S^T is already the B-operand layout PV needs: P never goes through LDS.
+//
+// K and V are first re-tiled once per call (pack_kernel) into "fragment order": for every block a
+// 16-byte piece per (fragment, lane) in exactly the order the LDS reads want them, so that a tile
+// moves global -> LDS as a straight copy and every LDS read is a conflict-free 1 KB wave read.
+// The V tile is stored transposed, with its key index permuted to match the accumulator layout:
+//     accumulator register r of kv-tile mt, lane l  <->  key 32*mt + 8*(r/4) + 4*(l/32) + r%4,
+//     query (l%32).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "jenga_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+  // round to nearest even; inputs are finite and non-negative or small, NaN does not occur here
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+
+// grid (M, batch*heads).  K tile -> fragment order; V tile -> transposed fragment order, pad rows zeroed.
+template <int BLK, int D>
+__global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                                                   uint4* __restrict__ kp, uint4* __restrict__ vp,
+                                                   const int32_t* __restrict__ blk_valid, int M, int n_pad) {
+  constexpr int KS = D / 16, PS = BLK / 16, CH = D / 8;
+  constexpr int TILE_CHUNKS = BLK * D / 8;
+  constexpr int LDV = D + 8;   // padded row length (elements) of the staged V tile
+  __shared__ uint16_t vl[BLK * LDV];
+  const int j = blockIdx.x, bh = blockIdx.y;
+  const int nv = blk_valid[j];
+  const size_t row0 = (size_t)bh * n_pad + (size_t)j * BLK;
+  const uint4* ksrc = (const uint4*)(k + row0 * D);
+  const uint4* vsrc = (const uint4*)(v + row0 * D);
+  uint4* kdst = kp + ((size_t)bh * M + j) * TILE_CHUNKS;
+  uint4* vdst = vp + ((size_t)bh * M + j) * TILE_CHUNKS;
+
+  for (int o = threadIdx.x; o < TILE_CHUNKS; o += 256) {
+    const int lane = o & 63, f = o >> 6;
+    const int ks = f % KS, mt = f / KS;
+    const int row = 32 * mt + (lane & 31);
+    kdst[o] = ksrc[row * CH + 2 * ks + (lane >> 5)];
+  }
+  for (int o = threadIdx.x; o < TILE_CHUNKS; o += 256) {
+    const int row = o / CH, cc = o % CH;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (row < nv) val = vsrc[o];
+    *(uint4*)&vl[row * LDV + cc * 8] = val;
+  }
+  __syncthreads();
+  for (int o = threadIdx.x; o < TILE_CHUNKS; o += 256) {
+    const int lane = o & 63, f = o >> 6;
+    const int ps = f % PS, dt = f / PS;
+    const int hl = lane >> 5, d = 32 * dt + (lane & 31);
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const int e = 2 * e2;
+      const int kv0 = 16 * ps + 8 * (e / 4) + 4 * hl + (e % 4);
+      w[e2] = (uint32_t)vl[kv0 * LDV + d] | ((uint32_t)vl[(kv0 + 1) * LDV + d] << 16);
+    }
+    vdst[o] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+template <int BLK, int D>
+struct AttnTraits {
+  static constexpr int NW = BLK / 32;          // wavefronts per workgroup
+  static constexpr int NTHR = NW * 64;
+  static constexpr int MT = BLK / 32;          // 32-key tiles per key block
+  static constexpr int KS = D / 16;            // k-steps of K Q^T
+  static constexpr int DT = D / 32;            // 32-channel tiles of the output
+  static constexpr int PS = BLK / 16;          // k-steps of V^T P^T
+  static constexpr int TILE_CHUNKS = BLK * D / 8;
+  static constexpr int CPT = TILE_CHUNKS / NTHR;   // 16-byte pieces per thread per tile
+  static constexpr int MIN_WAVES = (BLK == 128 && D == 128) ? 2 : 1;
+};
+
+template <int BLK, int D>
+__global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MIN_WAVES)) void attn_kernel(
+    const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
+    const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int M, int M_v, int n_pad, int chunk,
+    float scale_log2e, float bias_log2e) {
+  using TR = AttnTraits<BLK, D>;
+  constexpr int NTHR = TR::NTHR, MT = TR::MT, KS = TR::KS, DT = TR::DT, PS = TR::PS;
+  constexpr int TILE_CHUNKS = TR::TILE_CHUNKS, CPT = TR::CPT;
+  __shared__ u32x4 Ks[TILE_CHUNKS];
+  __shared__ u32x4 Vs[TILE_CHUNKS];
+
+  // Work mapping.  Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run
+  // of query blocks of the same head so that the key/value tiles its workgroups share stay in
+  // that XCD's L2, and keep the whole chip on one head at a time so the head's K and V stay in
+  // the last-level cache.  Within a head the text query blocks (dense rows) are started first.
+  const int n = blockIdx.x;
+  const int xcd = n & 7, s = n >> 3;
+  const int bh = s / chunk;
+  const int i_lin = xcd * chunk + s % chunk;
+  if (i_lin >= M) return;
+  int i = i_lin + M_v;
+  if (i >= M) i -= M;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int hl = lane >> 5, ql = lane & 31;
+  const int qrow = i * BLK + 32 * wave + ql;
+
+  bf16x8 qf[KS];
+  {
+    const u32x4* qp = (const u32x4*)(q + ((size_t)bh * n_pad + qrow) * D);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qp[2 * ks + hl]);
+  }
+
+  int cnt = sel_count[(size_t)bh * M + i];
+  cnt = min(max(cnt, 0), M);
+  const int32_t* idx = sel_index + ((size_t)bh * M + i) * M;
+  const u32x4* kbase = kp + (size_t)bh * M * TILE_CHUNKS;
+  const u32x4* vbase = vp + (size_t)bh * M * TILE_CHUNKS;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 O[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+
+  u32x4 stage[CPT];
+  if (cnt > 0) {
+    const int j0 = min(max(idx[0], 0), M - 1);
+    const u32x4* src = kbase + (size_t)j0 * TILE_CHUNKS + tid;
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) Ks[c * NTHR + tid] = stage[c];
+  }
+
+  for (int it = 0; it < cnt; ++it) {
+    const int j = min(max(idx[it], 0), M - 1);
+    {
+      const u32x4* src = vbase + (size_t)j * TILE_CHUNKS + tid;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
+    }
+    __syncthreads();   // K tile of this step is in LDS; every wave is past the previous PV
+
+    f32x16 S[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[mt][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, Ks[(mt * KS + ks) * 64 + lane]);
+        S[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], S[mt], 0, 0, 0);
+      }
+    }
+
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) Vs[c * NTHR + tid] = stage[c];
+    const bool more = it + 1 < cnt;
+    if (more) {
+      const int jn = min(max(idx[it + 1], 0), M - 1);
+      const u32x4* src = kbase + (size_t)jn * TILE_CHUNKS + tid;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
+    }
+
+    // ---- online softmax on S^T (lane = query row, registers = keys) ----
+    const int nv = blk_valid[j];
+    if (nv < BLK) {   // sequence-length mask: pad keys of a ragged block
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = 32 * mt + 8 * (r / 4) + 4 * hl + (r % 4);
+          if (kv >= nv) S[mt][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[mt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
+    const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float off = bias - m_new;
+    float rs = 0.f;
+    bf16x8 pb[PS];
+#pragma unroll
+    for (int ps = 0; ps < PS; ++ps) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2], scale_log2e, off));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2 + 1], scale_log2e, off));
+        rs += p0 + p1;
+        w[e2] = pack_bf16x2(p0, p1);
+      }
+      u32x4 pw = {w[0], w[1], w[2], w[3]};
+      pb[ps] = __builtin_bit_cast(bf16x8, pw);
+    }
+    l_run = fmaf(l_run, alpha, rs);
+    m_run = m_new;
+    if (__ballot(alpha != 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+    }
+
+    __syncthreads();   // V tile is in LDS; every wave is done reading the K tile
+
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int ps = 0; ps < PS; ++ps) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, Vs[(dt * PS + ps) * 64 + lane]);
+        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ps], O[dt], 0, 0, 0);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) Ks[c * NTHR + tid] = stage[c];
+    }
+  }
+
+  // ---- normalise and store: lane holds row qrow, channels 32*dt + 8*g + 4*hl + {0..3} ----
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const bool row_ok = (32 * wave + ql) < blk_valid[i] && l_tot > 0.f;
+  const float inv = row_ok ? 1.0f / l_tot : 0.f;
+  uint16_t* orow = out + ((size_t)bh * n_pad + qrow) * D;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 w;
+      w.x = row_ok ? pack_bf16x2(O[dt][4 * g] * inv, O[dt][4 * g + 1] * inv) : 0u;
+      w.y = row_ok ? pack_bf16x2(O[dt][4 * g + 2] * inv, O[dt][4 * g + 3] * inv) : 0u;
+      *(uint2*)(orow + 32 * dt + 8 * g + 4 * hl) = w;
+    }
+}
+
+template <int BLK, int D>
+int run_attention(const jenga_plan* p, const void* q, const void* k, const void* v, const int32_t* sel_count,
+                  const int32_t* sel_index, void* out, void* ws, hipStream_t st) {
+  const jenga_config& c = p->cfg;
+  const jenga_plan_info_t& f = p->info;
+  const int bh = c.batch * c.heads;
+  const size_t half = (((size_t)bh * f.N_pad * D * 2) + 255) & ~(size_t)255;
+  uint4* kp = (uint4*)ws;
+  uint4* vp = (uint4*)((char*)ws + half);
+  pack_kernel<BLK, D><<<dim3(f.M, bh), 256, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, kp, vp,
+                                                     p->d_blk_valid, f.M, f.N_pad);
+  const int chunk = (f.M + 7) / 8;
+  const float log2e = 1.4426950408889634f;
+  const float scale = log2e / sqrtf((float)D);
+  attn_kernel<BLK, D><<<dim3(bh * 8 * chunk), AttnTraits<BLK, D>::NTHR, 0, st>>>(
+      (const uint16_t*)q, (const u32x4*)kp, (const u32x4*)vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+      chunk, scale, c.text_bias * log2e);
+  return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
+}
+
+}  // namespace
+
+namespace jenga {
+
+int launch_attention(const jenga_plan* p, const void* q, const void* k, const void* v, const int32_t* sel_count,
+                     const int32_t* sel_index, void* out, void* ws, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int blk = p->cfg.block, d = p->cfg.head_dim;
+#define JENGA_ATTN(B, DD) \
+  if (blk == B && d == DD) return run_attention<B, DD>(p, q, k, v, sel_count, sel_index, out, ws, st)
+  JENGA_ATTN(128, 128);
+  JENGA_ATTN(64, 128);
+  JENGA_ATTN(32, 128);
+  JENGA_ATTN(128, 64);
+  JENGA_ATTN(64, 64);
+  JENGA_ATTN(32, 64);
+#undef JENGA_ATTN
+  return JENGA_EUNSUPPORTED;
+}
+
+}  // namespace jenga

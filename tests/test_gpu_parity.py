@@ -1,0 +1,180 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
+inputs.  Permutation, masks and index lists bit-exact; attention within max-abs 2e-2 and 1e-2 of the
+largest reference magnitude per head."""
+import numpy as np
+import pytest
+import torch
+
+import jenga_inputs as ji
+from oracle import jenga_oracle as jo
+import paper_2505_16864_amd as J
+from paper_2505_16864_amd.layer import CarveLayer
+from gpu_util import oracle_layout, to_f64, check_output, lists_from_gpu, check_lists_against_mask
+
+pytestmark = pytest.mark.gpu
+
+# small enough for the oracle to finish in seconds, large enough for several tiles and ragged tails
+CASES = {
+    "tiny": ji.WORKLOADS["tiny"],
+    "small": ji.WORKLOADS["small"],
+    "ragged_m32_d64": dict(T=3, H=5, W=7, n_text=40, batch=2, heads=3, head_dim=64, block=32, topk=0.3, p=0.3),
+    "ragged_m64_d128": dict(T=5, H=6, W=11, n_text=70, batch=1, heads=2, head_dim=128, block=64, topk=0.3, p=0.5),
+    "ragged_m128_d128": dict(T=7, H=9, W=13, n_text=200, batch=1, heads=3, head_dim=128, block=128, topk=0.25, p=0.3),
+    "m128_d64": dict(T=4, H=10, W=12, n_text=33, batch=1, heads=2, head_dim=64, block=128, topk=0.5, p=0.3),
+    "m64_d64_notext": dict(T=4, H=6, W=9, n_text=0, batch=1, heads=2, head_dim=64, block=64, topk=0.4, p=0.2),
+    "m32_d128": dict(T=2, H=7, W=9, n_text=5, batch=1, heads=2, head_dim=128, block=32, topk=0.2, p=0.6),
+    "wide_M80": dict(T=6, H=20, W=21, n_text=40, batch=1, heads=2, head_dim=64, block=32, topk=0.1, p=0.9),
+}
+
+
+def _run(name, seed=11, flags=7, text_bias=0.0, w_override=None):
+    w = dict(CASES[name])
+    if w_override:
+        w.update(w_override)
+    print("case", name, "seed", seed, "flags", flags, flush=True)
+    q, k, v = ji.make_qkv(w, seed)
+    layer = CarveLayer(w, "cuda:0", text_bias=text_bias, flags=flags, want_mask=True)
+    out = layer.forward(q.cuda(), k.cuda(), v.cuda())
+    torch.cuda.synchronize()
+    lay = oracle_layout(w, flags)
+    return w, (q, k, v), layer, out, lay
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_permute_and_unpermute_bit_exact(name):
+    w = CASES[name]
+    print("case", name, flush=True)
+    q, _, _ = ji.make_qkv(w, 5)
+    layer = CarveLayer(w, "cuda:0")
+    lay = oracle_layout(w)
+    qd = q.cuda()
+    layer.o_c.fill_(7.0)                      # pads must be overwritten with zeros
+    J.jenga_curve_permute(layer.plan, qd, layer.o_c)
+    torch.cuda.synchronize()
+    want = jo.permute(ji.bits(q), lay)
+    assert np.array_equal(ji.bits(layer.o_c), want)
+    layer.out_thw.fill_(3.0)
+    J.jenga_unpermute(layer.plan, layer.o_c, layer.out_thw)
+    torch.cuda.synchronize()
+    assert np.array_equal(ji.bits(layer.out_thw), ji.bits(q))
+    # exported tables equal the oracle's
+    perm = np.zeros(lay.N_v, dtype=np.int32)
+    inv = np.zeros(lay.N_v, dtype=np.int32)
+    adja = np.zeros(lay.M_v * lay.M_v, dtype=np.uint8)
+    J.jenga_plan_export(layer.plan, perm, inv, adja)
+    assert np.array_equal(perm, lay.perm) and np.array_equal(inv, lay.inv)
+    assert np.array_equal(adja.reshape(lay.M_v, lay.M_v).astype(bool), jo.adjacency_mask(lay))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_masks_lists_and_output(name):
+    w, (q, k, v), layer, out, lay = _run(name)
+    want_out, want_mask, want_oc = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"])
+    got_mask = layer.mask.cpu().numpy().astype(bool)
+    assert np.array_equal(got_mask, want_mask)
+    cnt, idx = lists_from_gpu(layer)
+    check_lists_against_mask(cnt, idx, want_mask)
+    check_output(to_f64(layer.o_c), want_oc, name + " curve side")
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), name + " thw side")
+    assert not ji.bits(layer.o_c)[:, :, ~lay.valid].any()       # pad query rows are exactly zero
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3, 4, 5, 6])
+def test_mask_switches(flags):
+    w, (q, k, v), layer, out, lay = _run("ragged_m32_d64", seed=12, flags=flags)
+    want_out, want_mask, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"])
+    assert np.array_equal(layer.mask.cpu().numpy().astype(bool), want_mask)
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), "flags %d" % flags)
+
+
+@pytest.mark.parametrize("topk,p", [(0.05, 0.0), (0.3, 0.0), (0.2, 0.5), (0.1, 0.9), (1.0, 0.3), (0.05, 0.99)])
+def test_selection_knobs(topk, p):
+    w, (q, k, v), layer, out, lay = _run("wide_M80", seed=13, w_override=dict(topk=topk, p=p))
+    qc = jo.permute(to_f64(q), lay)
+    kc = jo.permute(to_f64(k), lay)
+    want_mask, R = jo.build_mask(qc, kc, lay, p, return_R=True)
+    gap, cdist = jo.selection_margins(R, lay.K_top, p)
+    assert gap > 1e-10 and cdist > 1e-10          # the inputs leave float64 room to decide
+    assert np.array_equal(layer.mask.cpu().numpy().astype(bool), want_mask)
+    cnt, idx = lists_from_gpu(layer)
+    check_lists_against_mask(cnt, idx, want_mask)
+
+
+def test_all_blocks_selected_equals_dense_attention():
+    # p -> 1 selects every block: the kernel must reproduce Eq. 1
+    w, (q, k, v), layer, out, lay = _run("ragged_m64_d128", seed=14, w_override=dict(p=0.9999999))
+    assert layer.mask.cpu().numpy().all()
+    want = jo.dense_attention(to_f64(q), to_f64(k), to_f64(v))
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want.transpose(0, 2, 1, 3), "dense")
+
+
+def test_text_bias():
+    import math
+    beta = -0.5 * math.log(0.5625)
+    w, (q, k, v), layer, out, lay = _run("ragged_m32_d64", seed=15, text_bias=beta)
+    want_out, want_mask, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"], beta=beta)
+    base_out, _, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"], beta=0.0)
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), "text bias")
+    assert np.abs(want_out - base_out).max() > 5e-2      # the bias is visible at this tolerance
+
+
+def test_attention_with_given_lists_and_constant_values():
+    # feed the oracle's lists of a random mask (not produced by selection) and a constant V
+    w = dict(CASES["ragged_m128_d128"])
+    q, k, v = ji.make_qkv(w, 16)
+    v[:] = torch.tensor(np.linspace(-2, 2, w["head_dim"]), dtype=torch.bfloat16)
+    layer = CarveLayer(w, "cuda:0")
+    lay = oracle_layout(w)
+    rng = np.random.default_rng(0)
+    mask = rng.random((w["batch"], w["heads"], lay.M, lay.M)) < 0.4
+    mask[:, :, np.arange(lay.M), np.arange(lay.M)] = True
+    cnt, idx = jo.mask_to_lists(mask)
+    layer.permute_in(q.cuda(), k.cuda(), v.cuda())
+    layer.sel_count.copy_(torch.from_numpy(cnt))
+    layer.sel_index.copy_(torch.from_numpy(idx))
+    layer.attend()
+    torch.cuda.synchronize()
+    got = to_f64(layer.o_c)
+    want_row = to_f64(v[0, 0, 0])
+    assert np.abs(got[:, :, lay.valid] - want_row).max() <= 2e-2
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    check_output(got, jo.block_sparse_attention(qc, kc, vc, mask, lay), "given lists")
+
+
+def test_malformed_lists_do_not_fault():
+    w = dict(CASES["tiny"])
+    q, k, v = ji.make_qkv(w, 17)
+    layer = CarveLayer(w, "cuda:0")
+    layer.permute_in(q.cuda(), k.cuda(), v.cuda())
+    layer.sel_count.fill_(10 ** 6)            # clamped to M
+    layer.sel_index.fill_(-5)                 # clamped to block 0
+    layer.sel_index[:, :, :, 1] = 10 ** 6     # clamped to block M-1
+    layer.attend()
+    layer.sel_count.zero_()                   # no keys: zero rows
+    layer.o_c.fill_(1.0)
+    layer.attend()
+    torch.cuda.synchronize()
+    assert not ji.bits(layer.o_c).any()
+
+
+def test_workspace_and_alignment_errors():
+    w = dict(CASES["tiny"])
+    layer = CarveLayer(w, "cuda:0")
+    with pytest.raises(J.JengaError) as e:
+        J.jenga_select_blocks(layer.plan, layer.q_c, layer.k_c, layer.sel_count, layer.sel_index, None,
+                              layer.ws_select, layer.info.select_workspace_bytes - 1)
+    assert e.value.status == -3
+    with pytest.raises(J.JengaError) as e:
+        J.jenga_block_sparse_attn(layer.plan, layer.q_c, layer.k_c, layer.v_c, layer.sel_count, layer.sel_index,
+                                  layer.o_c, layer.ws_attn.data_ptr() + 16, layer.info.attn_workspace_bytes)
+    assert e.value.status == -1
+
+
+def test_deterministic():
+    w, (q, k, v), layer, out, lay = _run("ragged_m128_d128", seed=18)
+    first = ji.bits(out).copy()
+    first_idx = layer.sel_index.cpu().numpy().copy()
+    out2 = layer.forward(q.cuda(), k.cuda(), v.cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(ji.bits(out2), first)
+    assert np.array_equal(layer.sel_index.cpu().numpy(), first_idx)
