@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention-carving hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic layer input:
+    3 x jenga_curve_permute (Q, K, V)  ->  jenga_select_blocks  ->  jenga_block_sparse_attn
+    ->  jenga_unpermute
+with Q/K/V already resident in HBM.  The headline value is the time of what recurs per layer
+(select + attention); the permutes, which the paper pays once per DiT forward, are reported beside
+it.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, q, k, v, seconds_budget=20.0):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload."""
+    import numpy as np
+    import jenga_inputs as ji
+    from oracle import jenga_oracle as jo
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    t_all = time.time()
+    lay = jo.Layout(w["T"], w["H"], w["W"], w["n_text"], w["block"], w["topk"])
+    t_plan = time.time() - t_all
+    heads = w["heads"]
+    h = 0
+    qs, ks, vs = [jo.permute(jo.bf16_bits_to_f64(ji.bits(x[:, :, h:h + 1, :])), lay) for x in (q, k, v)]
+    t0 = time.time()
+    mask = jo.build_mask(qs, ks, lay, w["p"])
+    t_select_head = time.time() - t0
+    rng = np.random.default_rng(0)
+    order = rng.permutation(lay.M_v)
+    n_blocks, t0 = 0, time.time()
+    for i in order:
+        jo.attention_block(qs[0, 0], ks[0, 0], vs[0, 0], mask[0, 0, i], lay, int(i))
+        n_blocks += 1
+        if time.time() - t0 > seconds_budget:
+            break
+    t_attn = time.time() - t0
+    mean_sel = float(mask[0, 0, : lay.M_v].sum(-1).mean())
+    # extrapolate to the full layer: every head, every vision block at the sampled cost per block,
+    # text blocks at the dense cost (M / mean_sel times a sampled block)
+    per_block = t_attn / n_blocks
+    layer_s = heads * w["batch"] * (t_select_head + per_block * (lay.M_v + lay.M_c * lay.M / mean_sel))
+    return {"value": layer_s * 1e3, "unit": "ms per layer (extrapolated)", "cores": cores, "kind": "oracle",
+            "sample": "head 0: masks of all %d query blocks (%.2f s) + attention of %d random vision query blocks "
+                      "(%.2f s); scaled to %d heads x %d blocks; plan %.2f s not included"
+                      % (lay.M_v, t_select_head, n_blocks, t_attn, heads, lay.M, t_plan),
+            "measured_s": t_select_head + t_attn}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="hy720p")
+    ap.add_argument("--seed", type=int, default=5000)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists)")
+
+    import torch
+    import jenga_inputs as ji
+    from paper_2505_16864_amd.layer import CarveLayer
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: needs a GPU")
+    w = ji.WORKLOADS[args.workload]
+    dev = "cuda:0"
+    q, k, v = ji.make_qkv(w, args.seed, device=dev)
+    layer = CarveLayer(w, dev)
+    info = layer.info
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    names = ["permute_in", "select", "pack", "attn", "permute_out"]
+    acc = {n: 0.0 for n in names}
+    total_ms = 0.0
+    for it in range(args.warmup + args.steps):
+        marks = [ev() for _ in range(6)]
+        torch.cuda.synchronize()
+        marks[0].record()
+        layer.permute_in(q, k, v)
+        marks[1].record()
+        layer.select()
+        marks[2].record()
+        layer.pack()
+        marks[3].record()
+        layer.attend_packed()
+        marks[4].record()
+        layer.permute_out()
+        marks[5].record()
+        torch.cuda.synchronize()
+        if it >= args.warmup:
+            for n, a, b in zip(names, marks[:-1], marks[1:]):
+                acc[n] += a.elapsed_time(b)
+            total_ms += marks[0].elapsed_time(marks[5])
+    ms = {n: acc[n] / args.steps for n in names}
+    ms_step = total_ms / args.steps
+    layer_ms = ms["select"] + ms["pack"] + ms["attn"]
+
+    m, d, heads, batch = w["block"], w["head_dim"], w["heads"], w["batch"]
+    sel_total = int(layer.sel_count.sum().item())
+    executed_flop = 4.0 * m * m * d * sel_total              # QK^T and PV of every visited m x m tile
+    dense_flop = 4.0 * float(info.N_pad) ** 2 * d * heads * batch
+    density = sel_total / float(batch * heads * info.M * info.M)
+    attn_tflops = executed_flop / (ms["attn"] * 1e-3) / 1e12
+    tensor_bytes = 2.0 * (info.N_v + w["n_text"]) * heads * d * batch
+    permute_gbs = 2 * tensor_bytes * 4 / ((ms["permute_in"] + ms["permute_out"]) * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_traffic.json" % args.workload)
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+
+    out = {
+        "metric": "ms per block-sparse attention layer (select + attention)",
+        "value": layer_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "grid": [w["T"], w["H"], w["W"]], "n_text": w["n_text"],
+                   "heads": heads, "head_dim": d, "block": m, "topk": w["topk"], "p": w["p"],
+                   "tokens_padded": info.N_pad, "blocks": info.M, "seed": args.seed},
+        "ms": ms,
+        "executed_tflop": executed_flop / 1e12, "dense_equiv_tflop": dense_flop / 1e12,
+        "executed_tflops": attn_tflops, "dense_equiv_tflops": dense_flop / (ms["attn"] * 1e-3) / 1e12,
+        "layer_executed_tflops": executed_flop / (layer_ms * 1e-3) / 1e12,
+        "density": density, "mean_selected_blocks": sel_total / float(batch * heads * info.M),
+        "permute_gbs": permute_gbs,
+        "roofline": {"kernel": "attn_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

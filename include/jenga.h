@@ -143,10 +143,27 @@ int jenga_select_blocks(const jenga_plan* plan, const void* q_curve, const void*
  *   out_curve  : bf16 curve side, fully overwritten
  *   workspace  : at least attn_workspace_bytes, 256-byte aligned (K and V re-tiled for the
  *                matrix cores), contents undefined after
+ * Equivalent to jenga_pack_kv followed by jenga_block_sparse_attn_packed on the same workspace.
  */
 int jenga_block_sparse_attn(const jenga_plan* plan, const void* q, const void* k, const void* v,
                             const int32_t* sel_count, const int32_t* sel_index, void* out_curve,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * First half of jenga_block_sparse_attn: re-tiles K and V of every block (Alg. 4's "load key-value
+ * block") into the matrix-core fragment order inside `workspace`; pad rows of V are zeroed.
+ * A caller that attends several times to the same K and V (a sweep of k or p) packs once.
+ */
+int jenga_pack_kv(const jenga_plan* plan, const void* k, const void* v, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/*
+ * Second half of jenga_block_sparse_attn: the block-sparse attention kernel itself, reading K and V
+ * from a workspace filled by jenga_pack_kv for the same plan.  Other arguments as above.
+ */
+int jenga_block_sparse_attn_packed(const jenga_plan* plan, const void* q, const void* packed_kv_workspace,
+                                   size_t workspace_bytes, const int32_t* sel_count,
+                                   const int32_t* sel_index, void* out_curve, void* stream);
 
 /*
  * Eq. 2, z_thw = G^-1(z_blk): dst_thw[b][src(i)][h][:] = src_curve[b][h][i][:] for every valid

@@ -14,7 +14,8 @@ JENGA_FLAG_CONDITION = 2
 JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
-           "jenga_curve_permute", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_unpermute",
+           "jenga_curve_permute", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
+           "jenga_block_sparse_attn_packed", "jenga_unpermute",
            "jenga_strerror"]
 
 
@@ -52,6 +53,8 @@ def _load():
     lib.jenga_unpermute.argtypes = [vp, vp, vp, vp]
     lib.jenga_select_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp]
     lib.jenga_strerror.argtypes = [ctypes.c_int]
     lib.jenga_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -131,6 +134,17 @@ def jenga_block_sparse_attn(plan, q, k, v, sel_count, sel_index, out_curve, work
     _check(_lib.jenga_block_sparse_attn(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(sel_count), _ptr(sel_index),
                                         _ptr(out_curve), _ptr(workspace), workspace_bytes, stream),
            "jenga_block_sparse_attn")
+
+
+def jenga_pack_kv(plan, k, v, workspace, workspace_bytes, stream=None):
+    _check(_lib.jenga_pack_kv(plan, _ptr(k), _ptr(v), _ptr(workspace), workspace_bytes, stream), "jenga_pack_kv")
+
+
+def jenga_block_sparse_attn_packed(plan, q, workspace, workspace_bytes, sel_count, sel_index, out_curve,
+                                   stream=None):
+    _check(_lib.jenga_block_sparse_attn_packed(plan, _ptr(q), _ptr(workspace), workspace_bytes, _ptr(sel_count),
+                                               _ptr(sel_index), _ptr(out_curve), stream),
+           "jenga_block_sparse_attn_packed")
 
 
 def raw():

@@ -262,8 +262,7 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
 }
 
 template <int BLK, int D>
-int run_attention(const jenga_plan* p, const void* q, const void* k, const void* v, const int32_t* sel_count,
-                  const int32_t* sel_index, void* out, void* ws, hipStream_t st) {
+int run_pack(const jenga_plan* p, const void* k, const void* v, void* ws, hipStream_t st) {
   const jenga_config& c = p->cfg;
   const jenga_plan_info_t& f = p->info;
   const int bh = c.batch * c.heads;
@@ -272,11 +271,23 @@ int run_attention(const jenga_plan* p, const void* q, const void* k, const void*
   uint4* vp = (uint4*)((char*)ws + half);
   pack_kernel<BLK, D><<<dim3(f.M, bh), 256, 0, st>>>((const uint16_t*)k, (const uint16_t*)v, kp, vp,
                                                      p->d_blk_valid, f.M, f.N_pad);
+  return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
+}
+
+template <int BLK, int D>
+int run_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
+                  const int32_t* sel_index, void* out, hipStream_t st) {
+  const jenga_config& c = p->cfg;
+  const jenga_plan_info_t& f = p->info;
+  const int bh = c.batch * c.heads;
+  const size_t half = (((size_t)bh * f.N_pad * D * 2) + 255) & ~(size_t)255;
+  const u32x4* kp = (const u32x4*)ws;
+  const u32x4* vp = (const u32x4*)((const char*)ws + half);
   const int chunk = (f.M + 7) / 8;
   const float log2e = 1.4426950408889634f;
   const float scale = log2e / sqrtf((float)D);
   attn_kernel<BLK, D><<<dim3(bh * 8 * chunk), AttnTraits<BLK, D>::NTHR, 0, st>>>(
-      (const uint16_t*)q, (const u32x4*)kp, (const u32x4*)vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+      (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
       chunk, scale, c.text_bias * log2e);
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
@@ -285,19 +296,26 @@ int run_attention(const jenga_plan* p, const void* q, const void* k, const void*
 
 namespace jenga {
 
-int launch_attention(const jenga_plan* p, const void* q, const void* k, const void* v, const int32_t* sel_count,
-                     const int32_t* sel_index, void* out, void* ws, void* stream) {
+#define JENGA_FOR_SHAPES(X) X(128, 128) X(64, 128) X(32, 128) X(128, 64) X(64, 64) X(32, 64)
+
+int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int blk = p->cfg.block, d = p->cfg.head_dim;
-#define JENGA_ATTN(B, DD) \
-  if (blk == B && d == DD) return run_attention<B, DD>(p, q, k, v, sel_count, sel_index, out, ws, st)
-  JENGA_ATTN(128, 128);
-  JENGA_ATTN(64, 128);
-  JENGA_ATTN(32, 128);
-  JENGA_ATTN(128, 64);
-  JENGA_ATTN(64, 64);
-  JENGA_ATTN(32, 64);
-#undef JENGA_ATTN
+#define X(B, DD) \
+  if (blk == B && d == DD) return run_pack<B, DD>(p, k, v, ws, st);
+  JENGA_FOR_SHAPES(X)
+#undef X
+  return JENGA_EUNSUPPORTED;
+}
+
+int launch_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
+                     const int32_t* sel_index, void* out, void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  const int blk = p->cfg.block, d = p->cfg.head_dim;
+#define X(B, DD) \
+  if (blk == B && d == DD) return run_attention<B, DD>(p, q, ws, sel_count, sel_index, out, st);
+  JENGA_FOR_SHAPES(X)
+#undef X
   return JENGA_EUNSUPPORTED;
 }
 

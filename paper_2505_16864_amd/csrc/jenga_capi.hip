@@ -151,7 +151,26 @@ int jenga_block_sparse_attn(const jenga_plan* p, const void* q, const void* k, c
   if (!p || !q || !k || !v || !sel_count || !sel_index || !out_curve || !workspace) return JENGA_EINVAL;
   if (((uintptr_t)workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
-  return jenga::launch_attention(p, q, k, v, sel_count, sel_index, out_curve, workspace, stream);
+  const int rc = jenga::launch_pack(p, k, v, workspace, stream);
+  if (rc != JENGA_OK) return rc;
+  return jenga::launch_attention(p, q, workspace, sel_count, sel_index, out_curve, stream);
+}
+
+int jenga_pack_kv(const jenga_plan* p, const void* k, const void* v, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+  if (!p || !k || !v || !workspace) return JENGA_EINVAL;
+  if (((uintptr_t)workspace & 255u) != 0) return JENGA_EINVAL;
+  if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
+  return jenga::launch_pack(p, k, v, workspace, stream);
+}
+
+int jenga_block_sparse_attn_packed(const jenga_plan* p, const void* q, const void* packed_kv_workspace,
+                                   size_t workspace_bytes, const int32_t* sel_count, const int32_t* sel_index,
+                                   void* out_curve, void* stream) {
+  if (!p || !q || !packed_kv_workspace || !sel_count || !sel_index || !out_curve) return JENGA_EINVAL;
+  if (((uintptr_t)packed_kv_workspace & 255u) != 0) return JENGA_EINVAL;
+  if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
+  return jenga::launch_attention(p, q, packed_kv_workspace, sel_count, sel_index, out_curve, stream);
 }
 
 const char* jenga_strerror(int status) {

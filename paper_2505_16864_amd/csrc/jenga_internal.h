@@ -33,8 +33,8 @@ int build_host_tables(jenga_plan* plan);
 int launch_permute(const jenga_plan* p, const void* src, void* dst, bool forward, void* stream);
 int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_count,
                   int32_t* sel_index, uint8_t* mask, void* ws, void* stream);
-int launch_attention(const jenga_plan* p, const void* q, const void* k, const void* v,
-                     const int32_t* sel_count, const int32_t* sel_index, void* out, void* ws,
-                     void* stream);
+int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, void* stream);
+int launch_attention(const jenga_plan* p, const void* q, const void* packed_ws, const int32_t* sel_count,
+                     const int32_t* sel_index, void* out, void* stream);
 
 }  // namespace jenga

@@ -45,6 +45,13 @@ class CarveLayer:
         B.jenga_block_sparse_attn(self.plan, self.q_c, self.k_c, self.v_c, self.sel_count, self.sel_index,
                                   self.o_c, self.ws_attn, self.ws_attn.numel(), self._stream())
 
+    def pack(self):
+        B.jenga_pack_kv(self.plan, self.k_c, self.v_c, self.ws_attn, self.ws_attn.numel(), self._stream())
+
+    def attend_packed(self):
+        B.jenga_block_sparse_attn_packed(self.plan, self.q_c, self.ws_attn, self.ws_attn.numel(), self.sel_count,
+                                         self.sel_index, self.o_c, self._stream())
+
     def permute_out(self):
         B.jenga_unpermute(self.plan, self.o_c, self.out_thw, self._stream())
 
