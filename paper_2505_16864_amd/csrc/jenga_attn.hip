@@ -83,6 +83,19 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
   }
 }
 
+// Straight copy of one packed tile (global, fragment order) into LDS without passing through
+// registers: every lane hands the DMA path its own 16-byte global address, the data of a wave
+// lands contiguously (1 KB) behind the wave-uniform LDS base.  Completion is tracked by vmcnt.
+template <int NTHR, int CPT>
+__device__ inline void tile_to_lds(const u32x4* __restrict__ src, u32x4* lds, int tid, int wave) {
+#pragma unroll
+  for (int c = 0; c < CPT; ++c)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * NTHR + tid),
+                                     (__attribute__((address_space(3))) void*)(lds + c * NTHR + wave * 64), 16, 0, 0);
+}
+
+__device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
+
 template <int BLK, int D>
 struct AttnTraits {
   static constexpr int NW = BLK / 32;          // wavefronts per workgroup
@@ -120,7 +133,8 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
   int i = i_lin + M_v;
   if (i >= M) i -= M;
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets LDS bases live in SGPRs
   const int hl = lane >> 5, ql = lane & 31;
   const int qrow = i * BLK + 32 * wave + ql;
 
@@ -144,24 +158,16 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
 #pragma unroll
     for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
 
-  u32x4 stage[CPT];
   if (cnt > 0) {
     const int j0 = min(max(idx[0], 0), M - 1);
-    const u32x4* src = kbase + (size_t)j0 * TILE_CHUNKS + tid;
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) Ks[c * NTHR + tid] = stage[c];
+    tile_to_lds<NTHR, CPT>(kbase + (size_t)j0 * TILE_CHUNKS, Ks, tid, wave);
   }
 
   for (int it = 0; it < cnt; ++it) {
     const int j = min(max(idx[it], 0), M - 1);
-    {
-      const u32x4* src = vbase + (size_t)j * TILE_CHUNKS + tid;
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
-    }
+    wait_vmem();       // this wave's part of the K tile has landed
     __syncthreads();   // K tile of this step is in LDS; every wave is past the previous PV
+    tile_to_lds<NTHR, CPT>(vbase + (size_t)j * TILE_CHUNKS, Vs, tid, wave);
 
     f32x16 S[MT];
 #pragma unroll
@@ -173,16 +179,6 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
         const bf16x8 a = __builtin_bit_cast(bf16x8, Ks[(mt * KS + ks) * 64 + lane]);
         S[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], S[mt], 0, 0, 0);
       }
-    }
-
-#pragma unroll
-    for (int c = 0; c < CPT; ++c) Vs[c * NTHR + tid] = stage[c];
-    const bool more = it + 1 < cnt;
-    if (more) {
-      const int jn = min(max(idx[it + 1], 0), M - 1);
-      const u32x4* src = kbase + (size_t)jn * TILE_CHUNKS + tid;
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) stage[c] = src[c * NTHR];
     }
 
     // ---- online softmax on S^T (lane = query row, registers = keys) ----
@@ -232,7 +228,12 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
         for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
     }
 
+    wait_vmem();       // this wave's part of the V tile has landed
     __syncthreads();   // V tile is in LDS; every wave is done reading the K tile
+    if (it + 1 < cnt) {
+      const int jn = min(max(idx[it + 1], 0), M - 1);
+      tile_to_lds<NTHR, CPT>(kbase + (size_t)jn * TILE_CHUNKS, Ks, tid, wave);
+    }
 
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -241,10 +242,6 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
         const bf16x8 a = __builtin_bit_cast(bf16x8, Vs[(dt * PS + ps) * 64 + lane]);
         O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[ps], O[dt], 0, 0, 0);
       }
-    }
-    if (more) {
-#pragma unroll
-      for (int c = 0; c < CPT; ++c) Ks[c * NTHR + tid] = stage[c];
     }
   }
 
