@@ -96,6 +96,14 @@ __device__ inline void tile_to_lds(const u32x4* __restrict__ src, u32x4* lds, in
 
 __device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
 
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+
+// acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16)
+__device__ inline float dot2_ones(uint32_t packed_pair, float acc) {
+  const bf16x2v ones = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, packed_pair), ones, acc, false);
+}
+
 template <int BLK, int D>
 struct AttnTraits {
   static constexpr int NW = BLK / 32;          // wavefronts per workgroup
@@ -212,8 +220,8 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
       for (int e2 = 0; e2 < 4; ++e2) {
         const float p0 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2], scale_log2e, off));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2 + 1], scale_log2e, off));
-        rs += p0 + p1;
         w[e2] = pack_bf16x2(p0, p1);
+        rs = dot2_ones(w[e2], rs);   // row sum of the rounded P that PV multiplies
       }
       u32x4 pw = {w[0], w[1], w[2], w[3]};
       pb[ps] = __builtin_bit_cast(bf16x8, pw);
