@@ -269,6 +269,178 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// attn_h_kernel: blocks of 128 tokens, walked in half blocks of 64 keys.
+//
+// The matrix cores and the vector ALUs of a SIMD only overlap across wavefronts, so occupancy is
+// what keeps the MFMA pipe fed while other waves do their softmax.  A step over 64 keys needs half
+// the S and P registers and half the LDS of a step over 128, which lets three workgroups (twelve
+// wavefronts) live on a CU instead of two; everything else is attn_kernel: 4 waves x 32 query
+// rows, transposed products, K and V^T fragments straight from the packed tiles, DMA to LDS.
+// ---------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 3) void attn_h_kernel(
+    const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
+    const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int M, int M_v, int n_pad, int chunk,
+    float scale_log2e, float bias_log2e) {
+  constexpr int BLK = 128, KS = D / 16, DT = D / 32, PS = BLK / 16, MH = 2, PH = 4;
+  constexpr int TILE_CHUNKS = BLK * D / 8, HALF_CHUNKS = TILE_CHUNKS / 2, CPT = HALF_CHUNKS / 256;
+  __shared__ u32x4 Ks[HALF_CHUNKS];   // fragments (m2, ks) of the current 64 keys
+  __shared__ u32x4 Vs[HALF_CHUNKS];   // fragments (dt, p2) of the current 64 keys
+
+  const int nb = blockIdx.x;
+  const int xcd = nb & 7, sl = nb >> 3;
+  const int bh = sl / chunk;
+  const int i_lin = xcd * chunk + sl % chunk;
+  if (i_lin >= M) return;
+  int i = i_lin + M_v;
+  if (i >= M) i -= M;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hl = lane >> 5, ql = lane & 31;
+  const int qrow = i * BLK + 32 * wave + ql;
+
+  bf16x8 qf[KS];
+  {
+    const u32x4* qp = (const u32x4*)(q + ((size_t)bh * n_pad + qrow) * D);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, qp[2 * ks + hl]);
+  }
+
+  int cnt = sel_count[(size_t)bh * M + i];
+  cnt = min(max(cnt, 0), M);
+  const int steps = 2 * cnt;
+  const int32_t* idx = sel_index + ((size_t)bh * M + i) * M;
+  const u32x4* kbase = kp + (size_t)bh * M * TILE_CHUNKS;
+  const u32x4* vbase = vp + (size_t)bh * M * TILE_CHUNKS;
+
+  // K half h of block j is one contiguous run of the packed tile; V half h is PH fragments out of
+  // every PS of each channel tile: wave w copies fragments f = c*4 + w, f = dt*PH + p2
+  auto k_half_to_lds = [&](int j, int h) {
+    tile_to_lds<256, CPT>(kbase + (size_t)j * TILE_CHUNKS + h * HALF_CHUNKS, Ks, tid, wave);
+  };
+  auto v_half_to_lds = [&](int j, int h) {
+    const uint64_t b = (uint64_t)(vbase + (size_t)j * TILE_CHUNKS + (PH * h) * 64);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const char* base = (const char*)(((uint64_t)hi << 32) | lo);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int f = c * 4 + wave, dt = f / PH, p2 = f % PH;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(base + ((size_t)(dt * PS + p2) * 64 + lane) * 16),
+          (__attribute__((address_space(3))) void*)(Vs + f * 64), 16, 0, 0);
+    }
+  };
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x16 O[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+
+  if (cnt > 0) k_half_to_lds(min(max(idx[0], 0), M - 1), 0);
+
+  for (int st = 0; st < steps; ++st) {
+    const int h = st & 1;
+    const int j = min(max(idx[st >> 1], 0), M - 1);
+    wait_vmem();       // this wave's part of the K half has landed
+    __syncthreads();   // K half of this step is in LDS; every wave is past the previous PV
+    v_half_to_lds(j, h);
+
+    f32x16 S[MH];
+#pragma unroll
+    for (int m2 = 0; m2 < MH; ++m2) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) S[m2][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, Ks[(m2 * KS + ks) * 64 + lane]);
+        S[m2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], S[m2], 0, 0, 0);
+      }
+    }
+
+    // ---- online softmax on S^T (lane = query row, registers = keys) ----
+    const int nv = blk_valid[j];
+    if (nv < BLK) {   // sequence-length mask: pad keys of a ragged block
+      asm volatile("");   // a real, rarely taken branch
+#pragma unroll
+      for (int m2 = 0; m2 < MH; ++m2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int kv = 64 * h + 32 * m2 + 8 * (r / 4) + 4 * hl + (r % 4);
+          if (kv >= nv) S[m2][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int m2 = 0; m2 < MH; ++m2)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[m2][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
+    // a half block whose keys are all padding has mx = -inf; keep the arithmetic finite
+    const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
+    const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+    const float off = m_new == -INFINITY ? 0.f : bias - m_new;
+    float rs = 0.f;
+    bf16x8 pb[PH];
+#pragma unroll
+    for (int p2 = 0; p2 < PH; ++p2) {
+      uint32_t w[4];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2], scale_log2e, off));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2 + 1], scale_log2e, off));
+        w[e2] = pack_bf16x2(p0, p1);
+        rs = dot2_ones(w[e2], rs);
+      }
+      u32x4 pw = {w[0], w[1], w[2], w[3]};
+      pb[p2] = __builtin_bit_cast(bf16x8, pw);
+    }
+    l_run = fmaf(l_run, alpha, rs);
+    m_run = m_new;
+    if (__ballot(alpha != 1.0f)) {
+      asm volatile("");
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+    }
+
+    wait_vmem();       // this wave's part of the V half has landed
+    __syncthreads();   // V half is in LDS; every wave is done reading the K half
+    if (st + 1 < steps) k_half_to_lds(min(max(idx[(st + 1) >> 1], 0), M - 1), (st + 1) & 1);
+
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int p2 = 0; p2 < PH; ++p2) {
+        const bf16x8 a = __builtin_bit_cast(bf16x8, Vs[(dt * PH + p2) * 64 + lane]);
+        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[p2], O[dt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- normalise and store: lane holds row qrow, channels 32*dt + 8*g + 4*hl + {0..3} ----
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const bool row_ok = (32 * wave + ql) < blk_valid[i] && l_tot > 0.f;
+  const float inv = row_ok ? 1.0f / l_tot : 0.f;
+  uint16_t* orow = out + ((size_t)bh * n_pad + qrow) * D;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 w;
+      w.x = row_ok ? pack_bf16x2(O[dt][4 * g] * inv, O[dt][4 * g + 1] * inv) : 0u;
+      w.y = row_ok ? pack_bf16x2(O[dt][4 * g + 2] * inv, O[dt][4 * g + 3] * inv) : 0u;
+      *(uint2*)(orow + 32 * dt + 8 * g + 4 * hl) = w;
+    }
+}
+
 template <int BLK, int D>
 int run_pack(const jenga_plan* p, const void* k, const void* v, void* ws, hipStream_t st) {
   const jenga_config& c = p->cfg;
@@ -294,9 +466,14 @@ int run_attention(const jenga_plan* p, const void* q, const void* ws, const int3
   const int chunk = (f.M + 7) / 8;
   const float log2e = 1.4426950408889634f;
   const float scale = log2e / sqrtf((float)D);
-  attn_kernel<BLK, D><<<dim3(bh * 8 * chunk), AttnTraits<BLK, D>::NTHR, 0, st>>>(
-      (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
-      chunk, scale, c.text_bias * log2e);
+  if constexpr (BLK == 128)
+    attn_h_kernel<D><<<dim3(bh * 8 * chunk), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
+                                                          p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+                                                          chunk, scale, c.text_bias * log2e);
+  else
+    attn_kernel<BLK, D><<<dim3(bh * 8 * chunk), AttnTraits<BLK, D>::NTHR, 0, st>>>(
+        (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+        chunk, scale, c.text_bias * log2e);
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
 
