@@ -104,6 +104,28 @@ __device__ inline float dot2_ones(uint32_t packed_pair, float acc) {
   return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, packed_pair), ones, acc, false);
 }
 
+// Work mapping shared by the attention kernels.  The text query blocks of every (batch, head) are
+// dense rows, several times longer than a vision row: they are dealt out first, ahead of all vision
+// blocks, so that none of them starts late and runs on alone at the end.  The vision blocks follow
+// head by head; workgroups are dealt round-robin to the 8 XCDs, and each XCD gets a contiguous run
+// of query blocks of the head, so that the whole chip works on one head at a time (its K and V stay
+// in the last-level cache) and neighbouring query blocks, whose selections overlap, share an L2.
+// Returns false for the filler workgroups of the last run.
+__device__ inline bool map_work(int n, int n_bh, int M, int M_v, int chunk, int* bh, int* i) {
+  const int M_c = M - M_v;
+  const int n_text = n_bh * M_c;
+  if (n < n_text) {
+    *bh = n / M_c;
+    *i = M_v + n % M_c;
+    return true;
+  }
+  n -= n_text;
+  const int xcd = n & 7, s = n >> 3;
+  *bh = s / chunk;
+  *i = xcd * chunk + s % chunk;
+  return *i < M_v;
+}
+
 template <int BLK, int D>
 struct AttnTraits {
   static constexpr int NW = BLK / 32;          // wavefronts per workgroup
@@ -121,7 +143,8 @@ template <int BLK, int D>
 __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MIN_WAVES)) void attn_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
-    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int M, int M_v, int n_pad, int chunk,
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int n_bh, int M, int M_v, int n_pad,
+    int chunk,
     float scale_log2e, float bias_log2e) {
   using TR = AttnTraits<BLK, D>;
   constexpr int NTHR = TR::NTHR, MT = TR::MT, KS = TR::KS, DT = TR::DT, PS = TR::PS;
@@ -129,17 +152,8 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
   __shared__ u32x4 Ks[TILE_CHUNKS];
   __shared__ u32x4 Vs[TILE_CHUNKS];
 
-  // Work mapping.  Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run
-  // of query blocks of the same head so that the key/value tiles its workgroups share stay in
-  // that XCD's L2, and keep the whole chip on one head at a time so the head's K and V stay in
-  // the last-level cache.  Within a head the text query blocks (dense rows) are started first.
-  const int n = blockIdx.x;
-  const int xcd = n & 7, s = n >> 3;
-  const int bh = s / chunk;
-  const int i_lin = xcd * chunk + s % chunk;
-  if (i_lin >= M) return;
-  int i = i_lin + M_v;
-  if (i >= M) i -= M;
+  int bh, i;
+  if (!map_work(blockIdx.x, n_bh, M, M_v, chunk, &bh, &i)) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, lets LDS bases live in SGPRs
@@ -282,20 +296,16 @@ template <int D>
 __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
-    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int M, int M_v, int n_pad, int chunk,
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int n_bh, int M, int M_v, int n_pad,
+    int chunk,
     float scale_log2e, float bias_log2e) {
   constexpr int BLK = 128, KS = D / 16, DT = D / 32, PS = BLK / 16, MH = 2, PH = 4;
   constexpr int TILE_CHUNKS = BLK * D / 8, HALF_CHUNKS = TILE_CHUNKS / 2, CPT = HALF_CHUNKS / 256;
   __shared__ u32x4 Ks[HALF_CHUNKS];   // fragments (m2, ks) of the current 64 keys
   __shared__ u32x4 Vs[HALF_CHUNKS];   // fragments (dt, p2) of the current 64 keys
 
-  const int nb = blockIdx.x;
-  const int xcd = nb & 7, sl = nb >> 3;
-  const int bh = sl / chunk;
-  const int i_lin = xcd * chunk + sl % chunk;
-  if (i_lin >= M) return;
-  int i = i_lin + M_v;
-  if (i >= M) i -= M;
+  int bh, i;
+  if (!map_work(blockIdx.x, n_bh, M, M_v, chunk, &bh, &i)) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -463,16 +473,17 @@ int run_attention(const jenga_plan* p, const void* q, const void* ws, const int3
   const size_t half = (((size_t)bh * f.N_pad * D * 2) + 255) & ~(size_t)255;
   const u32x4* kp = (const u32x4*)ws;
   const u32x4* vp = (const u32x4*)((const char*)ws + half);
-  const int chunk = (f.M + 7) / 8;
+  const int chunk = (f.M_v + 7) / 8;                      // vision query blocks per XCD and head
+  const int n_wg = bh * f.M_c + bh * 8 * chunk;           // text blocks first, then the vision runs
   const float log2e = 1.4426950408889634f;
   const float scale = log2e / sqrtf((float)D);
   if constexpr (BLK == 128)
-    attn_h_kernel<D><<<dim3(bh * 8 * chunk), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
-                                                          p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+    attn_h_kernel<D><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
+                                                          p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
                                                           chunk, scale, c.text_bias * log2e);
   else
-    attn_kernel<BLK, D><<<dim3(bh * 8 * chunk), AttnTraits<BLK, D>::NTHR, 0, st>>>(
-        (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, f.M, f.M_v, f.N_pad,
+    attn_kernel<BLK, D><<<dim3(n_wg), AttnTraits<BLK, D>::NTHR, 0, st>>>(
+        (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
         chunk, scale, c.text_bias * log2e);
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
