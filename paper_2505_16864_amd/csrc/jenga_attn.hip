@@ -86,12 +86,33 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
 // Straight copy of one packed tile (global, fragment order) into LDS without passing through
 // registers: every lane hands the DMA path its own 16-byte global address, the data of a wave
 // lands contiguously (1 KB) behind the wave-uniform LDS base.  Completion is tracked by vmcnt.
+// One DMA instruction: every lane hands over its own 16-byte global address (wave-uniform 64-bit
+// base in SGPRs + 32-bit per-lane byte offset); the data of the wave lands contiguously (1 KB)
+// behind the wave-uniform LDS byte address in M0.  Written as asm so that the compiler does not
+// track these copies: it would otherwise order every later LDS read of the same array behind them
+// with a full vmcnt(0) wait, which defeats fetching ahead into a second buffer.  Completion is
+// tracked by vmcnt and waited for explicitly (wait_vmem / wait_vmem_but) before the barrier that
+// publishes a tile.
+__device__ inline void dma_1kb_to_lds(const void* uniform_base, uint32_t lane_byte_off, const void* lds_dst) {
+  const uint64_t b = (uint64_t)uniform_base;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  const uint64_t base = ((uint64_t)hi << 32) | lo;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_addr), "v"(lane_byte_off), "s"(base)
+               : "memory", "m0");
+}
+
+// Straight copy of one packed tile (global, fragment order) into LDS without passing through
+// registers.
 template <int NTHR, int CPT>
-__device__ inline void tile_to_lds(const u32x4* __restrict__ src, u32x4* lds, int tid, int wave) {
+__device__ inline void tile_to_lds(const u32x4* __restrict__ src_tile, u32x4* lds, int tid, int wave) {
 #pragma unroll
   for (int c = 0; c < CPT; ++c)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * NTHR + tid),
-                                     (__attribute__((address_space(3))) void*)(lds + c * NTHR + wave * 64), 16, 0, 0);
+    dma_1kb_to_lds((const char*)src_tile + (size_t)c * NTHR * 16, (uint32_t)tid * 16u, lds + c * NTHR + wave * 64);
 }
 
 __device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
@@ -332,16 +353,11 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     tile_to_lds<256, CPT>(kbase + (size_t)j * TILE_CHUNKS + h * HALF_CHUNKS, Ks, tid, wave);
   };
   auto v_half_to_lds = [&](int j, int h) {
-    const uint64_t b = (uint64_t)(vbase + (size_t)j * TILE_CHUNKS + (PH * h) * 64);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-    const char* base = (const char*)(((uint64_t)hi << 32) | lo);
+    const u32x4* vt = vbase + (size_t)j * TILE_CHUNKS + (PH * h) * 64;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       const int f = c * 4 + wave, dt = f / PH, p2 = f % PH;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(base + ((size_t)(dt * PS + p2) * 64 + lane) * 16),
-          (__attribute__((address_space(3))) void*)(Vs + f * 64), 16, 0, 0);
+      dma_1kb_to_lds(vt + (size_t)(dt * PS + p2) * 64, (uint32_t)lane * 16u, Vs + f * 64);
     }
   };
 
