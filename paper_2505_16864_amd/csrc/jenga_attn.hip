@@ -23,6 +23,9 @@
 
 #include "jenga_internal.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -304,6 +307,38 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
     }
 }
 
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// One 1 KB MFMA fragment (16 bytes per lane) from LDS, issued here and now: the compiler's own
+// scheduling reads one fragment, waits, multiplies, and so leaves the LDS latency open before
+// every MFMA.  Reads issued through lds_frag are complete only after lds_wait on their registers.
+template <int BYTE_OFF>
+__device__ __forceinline__ void lds_frag(u32x4& dst, uint32_t lane_addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(lane_addr), "n"(BYTE_OFF) : "memory");
+}
+__device__ __forceinline__ void lds_wait(u32x4 (&g)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]) : : "memory");
+}
+
+// max over the two lanes l and l ^ 32 (the two halves of a query row's keys), in the vector ALU
+__device__ inline float max_with_other_half(float x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (uint32_t)r[0]), __builtin_bit_cast(float, (uint32_t)r[1]));
+#else
+  return x;   // host pass only; never executed
+#endif
+}
+
 // ---------------------------------------------------------------------------------------------
 // attn_h_kernel: blocks of 128 tokens, walked in half blocks of 64 keys.
 //
@@ -318,8 +353,7 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
     const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int n_bh, int M, int M_v, int n_pad,
-    int chunk,
-    float scale_log2e, float bias_log2e) {
+    int chunk, int pad_v, int pad_c, float scale_log2e, float bias_log2e) {
   constexpr int BLK = 128, KS = D / 16, DT = D / 32, PS = BLK / 16, MH = 2, PH = 4;
   constexpr int TILE_CHUNKS = BLK * D / 8, HALF_CHUNKS = TILE_CHUNKS / 2, CPT = HALF_CHUNKS / 256;
   __shared__ u32x4 Ks[HALF_CHUNKS];   // fragments (m2, ks) of the current 64 keys
@@ -367,30 +401,55 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+  const uint32_t ks_lane = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)Ks + lane * 16;
+  const uint32_t vs_lane = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)Vs + lane * 16;
 
-  if (cnt > 0) k_half_to_lds(min(max(idx[0], 0), M - 1), 0);
+  // The block index of the next step is fetched a step ahead, and the valid-token count of a
+  // block follows from its index, so no step waits on a scalar load it has just issued.
+  int j_next = cnt > 0 ? min(max(idx[0], 0), M - 1) : 0;
+  if (cnt > 0) k_half_to_lds(j_next, 0);
 
   for (int st = 0; st < steps; ++st) {
     const int h = st & 1;
-    const int j = min(max(idx[st >> 1], 0), M - 1);
+    const int j = j_next;
     wait_vmem();       // this wave's part of the K half has landed
     __syncthreads();   // K half of this step is in LDS; every wave is past the previous PV
     v_half_to_lds(j, h);
 
+    // S^T = K Q^T.  Fragments come in groups of four, (m2, ks) = (e & 1, 2g + e / 2); group g + 1 is
+    // in flight while the MFMAs of group g run, and the two accumulators alternate.
     f32x16 S[MH];
 #pragma unroll
-    for (int m2 = 0; m2 < MH; ++m2) {
+    for (int m2 = 0; m2 < MH; ++m2)
 #pragma unroll
       for (int r = 0; r < 16; ++r) S[m2][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, Ks[(m2 * KS + ks) * 64 + lane]);
-        S[m2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], S[m2], 0, 0, 0);
-      }
+    {
+      constexpr int NG = KS / 2;
+      u32x4 A[2][4];
+      static_for<4>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        lds_frag<((e & 1) * KS + e / 2) * 1024>(A[0][e], ks_lane);
+      });
+      static_for<NG>([&](auto G) {
+        constexpr int g = decltype(G)::value;
+        lds_wait(A[g & 1]);
+        if constexpr (g + 1 < NG)
+          static_for<4>([&](auto E) {
+            constexpr int e = decltype(E)::value;
+            lds_frag<((e & 1) * KS + 2 * (g + 1) + e / 2) * 1024>(A[(g + 1) & 1][e], ks_lane);
+          });
+        static_for<4>([&](auto E) {
+          constexpr int e = decltype(E)::value, m2 = e & 1, ks = 2 * g + e / 2;
+          S[m2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[g & 1][e]), qf[ks], S[m2],
+                                                          0, 0, 0);
+        });
+      });
     }
 
+    j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
+
     // ---- online softmax on S^T (lane = query row, registers = keys) ----
-    const int nv = blk_valid[j];
+    const int nv = BLK - (j == M_v - 1 ? pad_v : (j == M - 1 ? pad_c : 0));
     if (nv < BLK) {   // sequence-length mask: pad keys of a ragged block
       asm volatile("");   // a real, rarely taken branch
 #pragma unroll
@@ -406,7 +465,7 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     for (int m2 = 0; m2 < MH; ++m2)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[m2][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = max_with_other_half(mx);
     const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
     // a half block whose keys are all padding has mx = -inf; keep the arithmetic finite
     const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
@@ -439,15 +498,30 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 
     wait_vmem();       // this wave's part of the V half has landed
     __syncthreads();   // V half is in LDS; every wave is done reading the K half
-    if (st + 1 < steps) k_half_to_lds(min(max(idx[(st + 1) >> 1], 0), M - 1), (st + 1) & 1);
+    if (st + 1 < steps) k_half_to_lds(j_next, (st + 1) & 1);
 
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-      for (int p2 = 0; p2 < PH; ++p2) {
-        const bf16x8 a = __builtin_bit_cast(bf16x8, Vs[(dt * PH + p2) * 64 + lane]);
-        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[p2], O[dt], 0, 0, 0);
-      }
+    // O^T += V^T P^T, fragments (dt, p2) = (2 (g / 2) + (e & 1), 2 (g % 2) + e / 2), pipelined as above
+    {
+      constexpr int NG = DT;
+      u32x4 A[2][4];
+      static_for<4>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        lds_frag<((e & 1) * PH + e / 2) * 1024>(A[0][e], vs_lane);
+      });
+      static_for<NG>([&](auto G) {
+        constexpr int g = decltype(G)::value;
+        lds_wait(A[g & 1]);
+        if constexpr (g + 1 < NG)
+          static_for<4>([&](auto E) {
+            constexpr int e = decltype(E)::value, g1 = g + 1;
+            lds_frag<((2 * (g1 / 2) + (e & 1)) * PH + 2 * (g1 % 2) + e / 2) * 1024>(A[g1 & 1][e], vs_lane);
+          });
+        static_for<4>([&](auto E) {
+          constexpr int e = decltype(E)::value, dt = 2 * (g / 2) + (e & 1), p2 = 2 * (g % 2) + e / 2;
+          O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[g & 1][e]), pb[p2], O[dt],
+                                                          0, 0, 0);
+        });
+      });
     }
   }
 
@@ -496,7 +570,7 @@ int run_attention(const jenga_plan* p, const void* q, const void* ws, const int3
   if constexpr (BLK == 128)
     attn_h_kernel<D><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
                                                           p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
-                                                          chunk, scale, c.text_bias * log2e);
+                                                          chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e);
   else
     attn_kernel<BLK, D><<<dim3(n_wg), AttnTraits<BLK, D>::NTHR, 0, st>>>(
         (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
