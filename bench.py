@@ -62,6 +62,28 @@ def cpu_baseline(w, q, k, v, seconds_budget=20.0):
             "measured_s": t_select_head + t_attn}
 
 
+def stage_switch_bench(dev, reps=20):
+    """The resolution switch between stages (Eq. 4) at the 540p -> 720p latent shape: HBM-bound, beside the layer."""
+    import torch
+    import jenga_inputs as ji
+    from paper_2505_16864_amd import binding as jb
+    w = ji.STAGE_SWITCHES["hy540to720"]
+    x, e, n = ji.make_latents(w, 7030, device=dev)
+    out = torch.empty_like(n)
+    stream = torch.cuda.current_stream().cuda_stream
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(2):
+        a.record()
+        for _ in range(reps):
+            jb.jenga_stage_switch(x, e, n, out, w["channels"], w["in"], w["out"], w["sigma"], stream)
+        b.record()
+        torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    nbytes = 4.0 * (2 * x.numel() + 2 * n.numel())
+    return {"workload": "hy540to720", "ms": ms, "algorithmic_bytes": nbytes, "gbs": nbytes / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,6 +168,7 @@ def main():
         "roofline": {"kernel": "attn_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
+    out["stage_switch"] = stage_switch_bench(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v)
     print(json.dumps(out))

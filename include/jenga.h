@@ -9,6 +9,7 @@
  *   jenga_select_blocks     B = B_top u B_cond u B_adja           Eq. 3, Alg. 3, appendix Eq. 5
  *   jenga_block_sparse_attn O = attention over the blocks of B    Alg. 4, Alg. 2, Eq. 1
  *   jenga_unpermute         z_thw = G^-1(z_blk)                   Eq. 2
+ *   jenga_stage_switch      resolution switch between stages      Eq. 4
  *
  * Conventions
  *   - All tensor arguments are DEVICE pointers unless a comment says "host".  The caller owns
@@ -170,6 +171,26 @@ int jenga_block_sparse_attn_packed(const jenga_plan* plan, const void* q, const 
  * position i; pad rows are dropped.  dst_thw is fully overwritten.
  */
 int jenga_unpermute(const jenga_plan* plan, const void* src_curve, void* dst_thw, void* stream);
+
+/*
+ * Progressive-resolution stage switch (Sec. 3.2, Eq. 4), one fused elementwise pass:
+ *   x_out = (1 - sigma_t) * U(x_t - sigma_t * eps_t) + sigma_t * eps_tilde
+ * U is 3D area interpolation from (T_in, H_in, W_in) to (T_out, H_out, W_out): along each axis with I
+ * input and O output cells, output cell o is the unweighted mean of input cells
+ * floor(o*I/O) .. ceil((o+1)*I/O) - 1 (for integer factors: replication); any sizes >= 1 are accepted,
+ * also smaller outputs.
+ *   x_t, eps_t : float32 [channels][T_in][H_in][W_in]   latent and the model's prediction at step t (batch
+ *                folded into channels), read only
+ *   eps_tilde  : float32 [channels][T_out][H_out][W_out] standard-normal draw supplied by the caller
+ *   x_out      : float32 [channels][T_out][H_out][W_out], fully overwritten; must not alias the inputs
+ *   sigma_t    : scheduler noise level in [0, 1]
+ * No plan is needed.  float32 arithmetic, window sums in (t, h, w) order.  Only enqueues work on `stream`.
+ * JENGA_EINVAL for null pointers, sizes < 1 or sigma_t outside [0, 1] (NaN included); JENGA_EUNSUPPORTED
+ * when an extent exceeds 2^14 or the output has more than 2^32 rows or 2^34 cells.
+ */
+int jenga_stage_switch(const float* x_t, const float* eps_t, const float* eps_tilde, float* x_out,
+                       int32_t channels, int32_t T_in, int32_t H_in, int32_t W_in, int32_t T_out,
+                       int32_t H_out, int32_t W_out, float sigma_t, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* jenga_strerror(int status);

@@ -73,3 +73,23 @@ def make_qkv(w, seed, device="cpu", n_terms=4, noise_std=0.5):
 def bits(t):
     """bf16 tensor -> numpy uint16 array of its bit patterns (host copy)."""
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+# Stage switches (Sec. 3.2, Eq. 4): latent shapes [channels, T, H, W] before patchification.  The last one
+# is the 540p -> 720p switch of a HunyuanVideo-like latent (16 channels, 33 latent frames, 8x spatial VAE).
+STAGE_SWITCHES = {
+    "tiny": {"channels": 3, "in": (3, 5, 7), "out": (4, 8, 10), "sigma": 0.6},
+    "ragged": {"channels": 2, "in": (5, 13, 11), "out": (5, 17, 16), "sigma": 0.35},
+    "down": {"channels": 2, "in": (4, 9, 10), "out": (2, 4, 7), "sigma": 0.9},
+    "hy540to720": {"channels": 16, "in": (33, 68, 120), "out": (33, 90, 160), "sigma": 0.7},
+}
+
+
+def make_latents(w, seed, device="cpu"):
+    """x_t, eps_t [channels, T, H, W] and eps_tilde [channels, T', H', W']: seeded N(0, 1) float32."""
+    g = torch.Generator().manual_seed(seed)
+    shp_in, shp_out = (w["channels"],) + tuple(w["in"]), (w["channels"],) + tuple(w["out"])
+    x_t = torch.randn(shp_in, generator=g, dtype=torch.float32)
+    eps_t = torch.randn(shp_in, generator=g, dtype=torch.float32)
+    eps_tilde = torch.randn(shp_out, generator=g, dtype=torch.float32)
+    return x_t.to(device), eps_t.to(device), eps_tilde.to(device)

@@ -15,7 +15,7 @@ JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
            "jenga_curve_permute", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
-           "jenga_block_sparse_attn_packed", "jenga_unpermute",
+           "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch",
            "jenga_strerror"]
 
 
@@ -55,6 +55,7 @@ def _load():
     lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp]
+    lib.jenga_stage_switch.argtypes = [vp, vp, vp, vp] + [ctypes.c_int32] * 7 + [ctypes.c_float, vp]
     lib.jenga_strerror.argtypes = [ctypes.c_int]
     lib.jenga_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -145,6 +146,13 @@ def jenga_block_sparse_attn_packed(plan, q, workspace, workspace_bytes, sel_coun
     _check(_lib.jenga_block_sparse_attn_packed(plan, _ptr(q), _ptr(workspace), workspace_bytes, _ptr(sel_count),
                                                _ptr(sel_index), _ptr(out_curve), stream),
            "jenga_block_sparse_attn_packed")
+
+
+def jenga_stage_switch(x_t, eps_t, eps_tilde, x_out, channels, in_shape, out_shape, sigma_t, stream=None):
+    """in_shape = (T_in, H_in, W_in), out_shape = (T_out, H_out, W_out); float32 device tensors."""
+    _check(_lib.jenga_stage_switch(_ptr(x_t), _ptr(eps_t), _ptr(eps_tilde), _ptr(x_out), channels,
+                                   *[int(v) for v in in_shape], *[int(v) for v in out_shape], float(sigma_t), stream),
+           "jenga_stage_switch")
 
 
 def raw():
