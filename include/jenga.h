@@ -112,6 +112,19 @@ int jenga_plan_tables(const jenga_config* cfg, jenga_plan_info_t* info, int32_t*
 int jenga_curve_permute(const jenga_plan* plan, const void* src_thw, void* dst_curve, void* stream);
 
 /*
+ * Eq. 2 applied to a per-token table that has to follow the tokens into curve order, such as the
+ * rotary position-embedding frequencies (appendix, implementation details, "Frequency re-ordering":
+ * f_blk = G(f); Alg. 1, the step that remaps the positional frequencies once per stage):
+ *   dst_rows[i][:] = src_rows[src(i)][:]   for every valid position i, 0 for pads.
+ * src_rows: [N_v + N_c][row_bytes] bytes in thw order (text rows last), read only.
+ * dst_rows: [N_pad][row_bytes], fully overwritten.  Both 16-byte aligned.
+ * row_bytes: a power of two in [16, 4096] (e.g. 128 float32 = 512), else JENGA_EUNSUPPORTED.
+ * The batch and heads of the plan play no part.
+ */
+int jenga_curve_permute_rows(const jenga_plan* plan, const void* src_rows, void* dst_rows, int32_t row_bytes,
+                             void* stream);
+
+/*
  * Alg. 3 with Alg. 2's rule for text queries.  For every (batch, head, query block i):
  *   i < M_v : mean-pool Q and K per block over their valid tokens (Eq. 3), R = softmax over all M
  *             key blocks of Q^.K^/sqrt(d_k); order by (R descending, index ascending);

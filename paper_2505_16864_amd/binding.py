@@ -14,7 +14,7 @@ JENGA_FLAG_CONDITION = 2
 JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
-           "jenga_curve_permute", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
+           "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
            "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch",
            "jenga_strerror"]
 
@@ -51,6 +51,7 @@ def _load():
     lib.jenga_plan_tables.argtypes = [ctypes.POINTER(jenga_config), ctypes.POINTER(jenga_plan_info_t), vp, vp, vp]
     lib.jenga_curve_permute.argtypes = [vp, vp, vp, vp]
     lib.jenga_unpermute.argtypes = [vp, vp, vp, vp]
+    lib.jenga_curve_permute_rows.argtypes = [vp, vp, vp, ctypes.c_int32, vp]
     lib.jenga_select_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -118,6 +119,11 @@ def jenga_plan_tables(cfg, perm=None, inv_perm=None, adja=None):
 
 def jenga_curve_permute(plan, src_thw, dst_curve, stream=None):
     _check(_lib.jenga_curve_permute(plan, _ptr(src_thw), _ptr(dst_curve), stream), "jenga_curve_permute")
+
+
+def jenga_curve_permute_rows(plan, src_rows, dst_rows, row_bytes, stream=None):
+    _check(_lib.jenga_curve_permute_rows(plan, _ptr(src_rows), _ptr(dst_rows), row_bytes, stream),
+           "jenga_curve_permute_rows")
 
 
 def jenga_unpermute(plan, src_curve, dst_thw, stream=None):

@@ -131,6 +131,13 @@ int jenga_curve_permute(const jenga_plan* p, const void* src_thw, void* dst_curv
   return jenga::launch_permute(p, src_thw, dst_curve, true, stream);
 }
 
+int jenga_curve_permute_rows(const jenga_plan* p, const void* src_rows, void* dst_rows, int32_t row_bytes,
+                             void* stream) {
+  if (!p || !src_rows || !dst_rows) return JENGA_EINVAL;
+  if (row_bytes < 16 || row_bytes > 4096 || (row_bytes & (row_bytes - 1)) != 0) return JENGA_EUNSUPPORTED;
+  return jenga::launch_permute_rows(p, src_rows, dst_rows, row_bytes, stream);
+}
+
 int jenga_unpermute(const jenga_plan* p, const void* src_curve, void* dst_thw, void* stream) {
   if (!p || !src_curve || !dst_thw) return JENGA_EINVAL;
   return jenga::launch_permute(p, src_curve, dst_thw, false, stream);

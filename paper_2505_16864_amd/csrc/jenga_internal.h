@@ -31,6 +31,7 @@ int build_host_tables(jenga_plan* plan);
 
 // Kernel launchers (defined in the .hip files).  All return a jenga_status.
 int launch_permute(const jenga_plan* p, const void* src, void* dst, bool forward, void* stream);
+int launch_permute_rows(const jenga_plan* p, const void* src, void* dst, int row_bytes, void* stream);
 int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_count,
                   int32_t* sel_index, uint8_t* mask, void* ws, void* stream);
 int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, void* stream);

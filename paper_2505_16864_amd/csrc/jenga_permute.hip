@@ -87,4 +87,14 @@ int launch_permute(const jenga_plan* p, const void* src, void* dst, bool forward
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
 
+int launch_permute_rows(const jenga_plan* p, const void* src, void* dst, int row_bytes, void* stream) {
+  // a per-token table is the one-head, one-batch case of the same kernel with a row of row_bytes/16 pieces
+  const int chunks = row_bytes / 16;
+  const int groups = 256 / chunks;
+  dim3 grid((p->info.N_pad + groups - 1) / groups, 1, 1);
+  permute_kernel<true><<<grid, 256, 0, (hipStream_t)stream>>>((const uint4*)src, (uint4*)dst, p->d_src_of_pos,
+                                                              p->info.N_v + p->cfg.n_text, p->info.N_pad, 1, chunks, 1);
+  return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
+}
+
 }  // namespace jenga

@@ -109,6 +109,7 @@ def test_null_arguments_return_einval_without_a_device():
     assert lib.jenga_plan_export(None, None, None, None) == -1
     assert lib.jenga_curve_permute(None, None, None, None) == -1
     assert lib.jenga_unpermute(None, None, None, None) == -1
+    assert lib.jenga_curve_permute_rows(None, None, None, 512, None) == -1
     assert lib.jenga_select_blocks(None, None, None, None, None, None, None, 0, None) == -1
     assert lib.jenga_block_sparse_attn(None, None, None, None, None, None, None, None, 0, None) == -1
     assert lib.jenga_pack_kv(None, None, None, None, 0, None) == -1
