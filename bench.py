@@ -84,6 +84,28 @@ def stage_switch_bench(dev, reps=20):
             "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
 
 
+def sustained_mfma_tflops(dev, seconds=0.15):
+    """What the matrix cores sustain on random bf16 operands under the power limit (MFMA-only loop)."""
+    import torch
+    from paper_2505_16864_amd import binding as jb
+    g = torch.Generator().manual_seed(99)
+    ops = torch.randn(65536, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
+    n_wg = 2 * torch.cuda.get_device_properties(0).multi_processor_count     # two waves per SIMD
+    sink = torch.empty(n_wg * 256, device=dev, dtype=torch.float32)
+    stream = torch.cuda.current_stream().cuda_stream
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters, rate = 20000, 0.0
+    for _ in range(3):            # calibrate the length, then measure a run of about `seconds`
+        a.record()
+        jb.jenga_mfma_probe(ops, sink, iters, n_wg, stream)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b)
+        rate = n_wg * 4 * iters * 4 * 32768.0 / (ms * 1e-3) / 1e12
+        iters = max(2, int(iters * seconds * 1e3 / ms) // 2 * 2)
+    return rate
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,9 +187,12 @@ def main():
         "layer_executed_tflops": executed_flop / (layer_ms * 1e-3) / 1e12,
         "density": density, "mean_selected_blocks": sel_total / float(batch * heads * info.M),
         "permute_gbs": permute_gbs,
-        "roofline": {"kernel": "attn_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"kernel": "attn_h_kernel<128>" if m == 128 else "attn_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
+    sustained = sustained_mfma_tflops(dev)
+    out["roofline"]["mfma_only_random_operands_tflops"] = sustained
+    out["roofline"]["frac_of_mfma_only"] = attn_tflops / sustained
     out["stage_switch"] = stage_switch_bench(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v)

@@ -205,6 +205,20 @@ int jenga_stage_switch(const float* x_t, const float* eps_t, const float* eps_ti
                        int32_t channels, int32_t T_in, int32_t H_in, int32_t W_in, int32_t T_out,
                        int32_t H_out, int32_t W_out, float sigma_t, void* stream);
 
+/*
+ * Measurement aid (no passage of the paper: it is the "MFMA-only" yardstick of the benchmark): runs
+ * n_workgroups x 4 wavefronts, each issuing 4 * iters independent v_mfma_f32_32x32x16_bf16 (32,768 FLOP
+ * each) on fragments taken from `operands_bf16`, and writes one float per thread to `sink` so that the
+ * work is not optimised away.  The caller times it; with random operands and >= 100 ms of work the rate
+ * is what the matrix cores sustain under the part's power limit.
+ *   operands_bf16 : device, >= 65,536 bytes of bf16 values, 16-byte aligned, read only
+ *   sink          : device, >= n_workgroups * 256 floats, overwritten
+ *   iters         : even, >= 2;  n_workgroups in [1, 65536]
+ * JENGA_EINVAL / JENGA_EWORKSPACE on bad arguments; only enqueues work on `stream`.
+ */
+int jenga_mfma_probe(const void* operands_bf16, size_t operand_bytes, float* sink, size_t sink_floats,
+                     int32_t iters, int32_t n_workgroups, void* stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char* jenga_strerror(int status);
 

@@ -15,7 +15,7 @@ JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
            "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
-           "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch",
+           "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch", "jenga_mfma_probe",
            "jenga_strerror"]
 
 
@@ -57,6 +57,7 @@ def _load():
     lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp]
     lib.jenga_stage_switch.argtypes = [vp, vp, vp, vp] + [ctypes.c_int32] * 7 + [ctypes.c_float, vp]
+    lib.jenga_mfma_probe.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp]
     lib.jenga_strerror.argtypes = [ctypes.c_int]
     lib.jenga_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -159,6 +160,12 @@ def jenga_stage_switch(x_t, eps_t, eps_tilde, x_out, channels, in_shape, out_sha
     _check(_lib.jenga_stage_switch(_ptr(x_t), _ptr(eps_t), _ptr(eps_tilde), _ptr(x_out), channels,
                                    *[int(v) for v in in_shape], *[int(v) for v in out_shape], float(sigma_t), stream),
            "jenga_stage_switch")
+
+
+def jenga_mfma_probe(operands_bf16, sink, iters, n_workgroups, stream=None):
+    """operands_bf16: device bf16 tensor of >= 32768 elements; sink: device float32 tensor of >= n_workgroups*256."""
+    _check(_lib.jenga_mfma_probe(_ptr(operands_bf16), operands_bf16.numel() * operands_bf16.element_size(),
+                                 _ptr(sink), sink.numel(), iters, n_workgroups, stream), "jenga_mfma_probe")
 
 
 def raw():

@@ -115,4 +115,5 @@ def test_null_arguments_return_einval_without_a_device():
     assert lib.jenga_pack_kv(None, None, None, None, 0, None) == -1
     assert lib.jenga_block_sparse_attn_packed(None, None, None, 0, None, None, None, None) == -1
     assert lib.jenga_stage_switch(None, None, None, None, 1, 1, 1, 1, 1, 1, 1, 0.5, None) == -1
+    assert lib.jenga_mfma_probe(None, 0, None, 0, 2, 1, None) == -1
     assert lib.jenga_plan_destroy(None) == 0
