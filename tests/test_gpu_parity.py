@@ -23,6 +23,8 @@ CASES = {
     "m128_d64": dict(T=4, H=10, W=12, n_text=33, batch=1, heads=2, head_dim=64, block=128, topk=0.5, p=0.3),
     "m64_d64_notext": dict(T=4, H=6, W=9, n_text=0, batch=1, heads=2, head_dim=64, block=64, topk=0.4, p=0.2),
     "m32_d128": dict(T=2, H=7, W=9, n_text=5, batch=1, heads=2, head_dim=128, block=32, topk=0.2, p=0.6),
+    "single_block": dict(T=1, H=2, W=3, n_text=0, batch=1, heads=1, head_dim=64, block=32, topk=0.3, p=0.3),
+    "one_token_each": dict(T=1, H=1, W=1, n_text=1, batch=2, heads=2, head_dim=128, block=128, topk=1.0, p=0.0),
     "wide_M80": dict(T=6, H=20, W=21, n_text=40, batch=1, heads=2, head_dim=64, block=32, topk=0.1, p=0.9),
 }
 
