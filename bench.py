@@ -135,6 +135,7 @@ def main():
 
     names = ["permute_in", "select", "pack", "attn", "permute_out"]
     acc = {n: 0.0 for n in names}
+    samples = {n: [] for n in names}
     total_ms = 0.0
     for it in range(args.warmup + args.steps):
         marks = [ev() for _ in range(6)]
@@ -153,7 +154,9 @@ def main():
         torch.cuda.synchronize()
         if it >= args.warmup:
             for n, a, b in zip(names, marks[:-1], marks[1:]):
-                acc[n] += a.elapsed_time(b)
+                t = a.elapsed_time(b)
+                acc[n] += t
+                samples[n].append(t)
             total_ms += marks[0].elapsed_time(marks[5])
     ms = {n: acc[n] / args.steps for n in names}
     ms_step = total_ms / args.steps
@@ -182,6 +185,8 @@ def main():
                    "heads": heads, "head_dim": d, "block": m, "topk": w["topk"], "p": w["p"],
                    "tokens_padded": info.N_pad, "blocks": info.M, "seed": args.seed},
         "ms": ms,
+        "ms_median": {n: sorted(samples[n])[len(samples[n]) // 2] for n in names},
+        "ms_min": {n: min(samples[n]) for n in names},
         "executed_tflop": executed_flop / 1e12, "dense_equiv_tflop": dense_flop / 1e12,
         "executed_tflops": attn_tflops, "dense_equiv_tflops": dense_flop / (ms["attn"] * 1e-3) / 1e12,
         "layer_executed_tflops": executed_flop / (layer_ms * 1e-3) / 1e12,
