@@ -21,10 +21,10 @@
 
 #include <cmath>
 
-#include "jenga_internal.h"
-
 #include <type_traits>
 #include <utility>
+
+#include "jenga_internal.h"
 
 namespace {
 
@@ -86,16 +86,12 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
   }
 }
 
-// Straight copy of one packed tile (global, fragment order) into LDS without passing through
-// registers: every lane hands the DMA path its own 16-byte global address, the data of a wave
-// lands contiguously (1 KB) behind the wave-uniform LDS base.  Completion is tracked by vmcnt.
-// One DMA instruction: every lane hands over its own 16-byte global address (wave-uniform 64-bit
-// base in SGPRs + 32-bit per-lane byte offset); the data of the wave lands contiguously (1 KB)
-// behind the wave-uniform LDS byte address in M0.  Written as asm so that the compiler does not
-// track these copies: it would otherwise order every later LDS read of the same array behind them
-// with a full vmcnt(0) wait, which defeats fetching ahead into a second buffer.  Completion is
-// tracked by vmcnt and waited for explicitly (wait_vmem / wait_vmem_but) before the barrier that
-// publishes a tile.
+// One DMA instruction, global -> LDS without passing through registers: every lane hands over its
+// own 16-byte global address (wave-uniform 64-bit base in SGPRs + 32-bit per-lane byte offset); the
+// data of the wave lands contiguously (1 KB) behind the wave-uniform LDS byte address in M0.
+// Written as asm so that the compiler does not track these copies: it would otherwise order every
+// later LDS read of the same array behind them with a full vmcnt(0) wait.  Completion is tracked by
+// vmcnt and waited for explicitly (wait_vmem) before the barrier that publishes a tile.
 __device__ inline void dma_1kb_to_lds(const void* uniform_base, uint32_t lane_byte_off, const void* lds_dst) {
   const uint64_t b = (uint64_t)uniform_base;
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
