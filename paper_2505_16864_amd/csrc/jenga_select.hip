@@ -70,24 +70,27 @@ __global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ 
   }
 }
 
-// S[bh][i][j] = sum_d qh[bh][i][d] * kh[bh][j][d] / sqrt(D); 64 x 64 tile per workgroup, 4 x 4 per thread
+// S[bh][i][j] = sum_d qh[bh][i][d] * kh[bh][j][d] / sqrt(D).  128 x 128 tile per workgroup, 8 x 8 per
+// thread with rows ty + 16 r and columns tx + 16 c: the 16 lanes that differ in tx read consecutive
+// doubles of a K^ row slice (no bank conflicts) and share one address of the Q^ slice (broadcast),
+// and 64 FMAs stand against 16 LDS reads.
 template <int D>
 __global__ __launch_bounds__(256) void scores_kernel(const double* __restrict__ qh, const double* __restrict__ kh,
                                                      double* __restrict__ S, int M_v, int M) {
-  constexpr int DC = 16;
-  __shared__ double As[DC][65];
-  __shared__ double Bs[DC][65];
+  constexpr int DC = 8, T = 128;
+  __shared__ double As[DC][T];
+  __shared__ double Bs[DC][T];
   const int bh = blockIdx.z;
-  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  const int i0 = blockIdx.y * T, j0 = blockIdx.x * T;
   const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
-  const int lr = threadIdx.x / 4, ld = (threadIdx.x % 4) * 4;   // loader: row, first of 4 d's
+  const int lr = threadIdx.x / 2, ld = (threadIdx.x % 2) * 4;   // loader: row of the tile, first of 4 d's
   const double* qa = qh + ((size_t)bh * M_v + min(i0 + lr, M_v - 1)) * D + ld;
   const double* kb = kh + ((size_t)bh * M + min(j0 + lr, M - 1)) * D + ld;
-  double acc[4][4];
+  double acc[8][8];
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
+  for (int r = 0; r < 8; ++r)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) acc[r][c] = 0.0;
+    for (int c = 0; c < 8; ++c) acc[r][c] = 0.0;
   for (int d0 = 0; d0 < D; d0 += DC) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -97,26 +100,26 @@ __global__ __launch_bounds__(256) void scores_kernel(const double* __restrict__ 
     __syncthreads();
 #pragma unroll
     for (int dd = 0; dd < DC; ++dd) {
-      double a[4], b[4];
+      double a[8], b[8];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) a[r] = As[dd][ty * 4 + r];
+      for (int r = 0; r < 8; ++r) a[r] = As[dd][ty + 16 * r];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) b[c] = Bs[dd][tx * 4 + c];
+      for (int c = 0; c < 8; ++c) b[c] = Bs[dd][tx + 16 * c];
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
+      for (int r = 0; r < 8; ++r)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) acc[r][c] = fma(a[r], b[c], acc[r][c]);
+        for (int c = 0; c < 8; ++c) acc[r][c] = fma(a[r], b[c], acc[r][c]);
     }
     __syncthreads();
   }
   const double inv = 1.0 / sqrt((double)D);
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int i = i0 + ty * 4 + r;
+  for (int r = 0; r < 8; ++r) {
+    const int i = i0 + ty + 16 * r;
     if (i >= M_v) continue;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const int j = j0 + tx * 4 + c;
+    for (int c = 0; c < 8; ++c) {
+      const int j = j0 + tx + 16 * c;
       if (j < M) S[((size_t)bh * M_v + i) * M + j] = acc[r][c] * inv;
     }
   }
@@ -263,7 +266,7 @@ int run_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_c
   if (f.M_v > 0) {
     pool_kernel<D><<<dim3(f.M_v, bh), 256, 0, st>>>((const uint16_t*)q, qh, p->d_blk_valid, f.N_pad, c.block, f.M_v);
     pool_kernel<D><<<dim3(f.M, bh), 256, 0, st>>>((const uint16_t*)k, kh, p->d_blk_valid, f.N_pad, c.block, f.M);
-    scores_kernel<D><<<dim3((f.M + 63) / 64, (f.M_v + 63) / 64, bh), 256, 0, st>>>(qh, kh, S, f.M_v, f.M);
+    scores_kernel<D><<<dim3((f.M + 127) / 128, (f.M_v + 127) / 128, bh), 256, 0, st>>>(qh, kh, S, f.M_v, f.M);
   }
   const int n_rows = bh * f.M;
   const dim3 grid((n_rows + 3) / 4);
