@@ -35,28 +35,44 @@ __device__ inline double wave_max(double v) {
   return v;
 }
 
-// grid (n_blk, batch*heads); x: curve side [bh][n_pad][D]; out: [bh][n_blk][D]
+// grid (M, batch*heads, 2): z = 0 pools Q (vision blocks only), z = 1 pools K (all blocks).
+// q, k: curve side [bh][n_pad][D]; qh: [bh][M_v][D]; kh: [bh][M][D].  A thread issues up to four row
+// loads before it adds them, so that enough bytes are in flight to stream from HBM.
 template <int D>
-__global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ x, double* __restrict__ out,
-                                                   const int32_t* __restrict__ blk_valid, int n_pad, int m,
-                                                   int n_blk) {
+__global__ __launch_bounds__(256) void pool_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                   double* __restrict__ qh, double* __restrict__ kh,
+                                                   const int32_t* __restrict__ blk_valid, int n_pad, int m, int M_v,
+                                                   int M) {
   constexpr int CH = D / 8;      // 16-byte chunks per row
-  constexpr int G = 256 / CH;    // rows in flight
+  constexpr int G = 256 / CH;    // rows in flight per pass
   __shared__ double red[G][D];
   const int j = blockIdx.x, bh = blockIdx.y;
+  const bool is_q = blockIdx.z == 0;
+  if (is_q && j >= M_v) return;
+  const uint16_t* x = is_q ? q : k;
+  double* out = is_q ? qh : kh;
+  const int n_blk = is_q ? M_v : M;
   const int c = threadIdx.x % CH, g = threadIdx.x / CH;
   const int nv = blk_valid[j];
   double acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.0;
   const uint4* base = (const uint4*)(x + ((size_t)bh * n_pad + (size_t)j * m) * D);
-  for (int r = g; r < nv; r += G) {
-    const uint4 v = base[(size_t)r * CH + c];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  for (int r0 = g; r0 < nv; r0 += 4 * G) {
+    uint4 v[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc[2 * e] += bf16_bits_to_double(w[e] & 0xFFFFu);
-      acc[2 * e + 1] += bf16_bits_to_double(w[e] >> 16);
+    for (int u = 0; u < 4; ++u) {
+      const int r = r0 + u * G;
+      v[u] = r < nv ? base[(size_t)r * CH + c] : make_uint4(0, 0, 0, 0);   // +0.0 for the rows past the end
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += bf16_bits_to_double(w[e] & 0xFFFFu);
+        acc[2 * e + 1] += bf16_bits_to_double(w[e] >> 16);
+      }
     }
   }
 #pragma unroll
@@ -264,8 +280,8 @@ int run_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_c
   w += align256((size_t)bh * f.M * D * 8);
   double* S = (double*)w;
   if (f.M_v > 0) {
-    pool_kernel<D><<<dim3(f.M_v, bh), 256, 0, st>>>((const uint16_t*)q, qh, p->d_blk_valid, f.N_pad, c.block, f.M_v);
-    pool_kernel<D><<<dim3(f.M, bh), 256, 0, st>>>((const uint16_t*)k, kh, p->d_blk_valid, f.N_pad, c.block, f.M);
+    pool_kernel<D><<<dim3(f.M, bh, 2), 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, qh, kh, p->d_blk_valid,
+                                                    f.N_pad, c.block, f.M_v, f.M);
     scores_kernel<D><<<dim3((f.M + 127) / 128, (f.M_v + 127) / 128, bh), 256, 0, st>>>(qh, kh, S, f.M_v, f.M);
   }
   const int n_rows = bh * f.M;
