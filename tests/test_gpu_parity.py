@@ -81,6 +81,15 @@ def test_masks_lists_and_output(name):
     assert not ji.bits(layer.o_c)[:, :, ~lay.valid].any()       # pad query rows are exactly zero
 
 
+@pytest.mark.parametrize("seed", list(range(100, 108)))
+@pytest.mark.parametrize("name", ["ragged_m128_d128", "ragged_m32_d64"])
+def test_more_seeds(name, seed):
+    w, (q, k, v), layer, out, lay = _run(name, seed=seed)
+    want_out, want_mask, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"])
+    assert np.array_equal(layer.mask.cpu().numpy().astype(bool), want_mask)
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), "%s seed %d" % (name, seed))
+
+
 @pytest.mark.parametrize("flags", [0, 1, 2, 3, 4, 5, 6])
 def test_mask_switches(flags):
     w, (q, k, v), layer, out, lay = _run("ragged_m32_d64", seed=12, flags=flags)
