@@ -84,6 +84,9 @@ STAGE_SWITCHES = {
     "tiny": {"channels": 3, "in": (3, 5, 7), "out": (4, 8, 10), "sigma": 0.6},
     "ragged": {"channels": 2, "in": (5, 13, 11), "out": (5, 17, 16), "sigma": 0.35},
     "down": {"channels": 2, "in": (4, 9, 10), "out": (2, 4, 7), "sigma": 0.9},
+    "down_w16": {"channels": 3, "in": (4, 12, 16), "out": (2, 5, 8), "sigma": 0.45},      # rows of 16: staged in LDS
+    "up_w12": {"channels": 2, "in": (3, 8, 12), "out": (4, 11, 18), "sigma": 0.55},         # W_out not a multiple of 4
+    "up_wide": {"channels": 1, "in": (2, 5, 1024), "out": (2, 7, 1366), "sigma": 0.2},      # more than 256 quads per row
     "hy540to720": {"channels": 16, "in": (33, 68, 120), "out": (33, 90, 160), "sigma": 0.7},
 }
 

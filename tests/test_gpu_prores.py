@@ -25,7 +25,7 @@ def run(w, seed, sigma=None):
     return out.cpu().numpy().astype(np.float64), want
 
 
-@pytest.mark.parametrize("name", ["tiny", "ragged", "down"])
+@pytest.mark.parametrize("name", ["tiny", "ragged", "down", "down_w16", "up_w12", "up_wide"])
 @pytest.mark.parametrize("seed", [0, 1])
 def test_small_cases(name, seed):
     got, want = run(ji.STAGE_SWITCHES[name], 7000 + seed)
