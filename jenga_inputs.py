@@ -30,6 +30,7 @@ WORKLOADS = {
     "hy_lowres":   dict(T=33, H=24, W=42, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3),
     "hy720p":      dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3),
     "hy720p_k10":  dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.10, p=0.3),
+    "wan480p_p90": dict(T=21, H=30, W=52, n_text=512, batch=1, heads=40, head_dim=128, block=128, topk=0.30, p=0.9),
     "hy720p_k20":  dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.20, p=0.3),
     # the largest block count the library takes (M = 2048): 2032 vision blocks of 32 tokens + 16 text blocks
     "max_blocks": {"T": 8, "H": 64, "W": 127, "n_text": 512, "batch": 1, "heads": 2, "head_dim": 64, "block": 32,

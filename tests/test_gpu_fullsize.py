@@ -27,7 +27,7 @@ def _qkv(name, seed):
     return _inputs[key]
 
 
-@pytest.mark.parametrize("name,seed", [("wan480p", 3000), ("hy_lowres", 4000), ("hy720p", 5000), ("hy720p_k10", 5000), ("hy720p_k20", 5000),
+@pytest.mark.parametrize("name,seed", [("wan480p", 3000), ("hy_lowres", 4000), ("hy720p", 5000), ("hy720p_k10", 5000), ("hy720p_k20", 5000), ("wan480p_p90", 3100),
                                        ("max_blocks", 6000)])
 def test_full_size(name, seed):
     w = ji.WORKLOADS[name]
