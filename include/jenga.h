@@ -153,7 +153,8 @@ int jenga_select_blocks(const jenga_plan* plan, const void* q_curve, const void*
  *   q, k, v    : bf16 curve side, read only
  *   sel_count, sel_index : as written by jenga_select_blocks.  Counts are clamped to [0, M] and
  *                indices to [0, M) on the device, so a malformed list cannot cause an access
- *                out of range; a count of 0 gives zero rows
+ *                out of range; a count of 0 gives zero rows.  The order of a list does not matter
+ *                beyond rounding (any permutation of the same blocks is accepted)
  *   out_curve  : bf16 curve side, fully overwritten
  *   workspace  : at least attn_workspace_bytes, 256-byte aligned (K and V re-tiled for the
  *                matrix cores), contents undefined after

@@ -152,6 +152,31 @@ def test_attention_with_given_lists_and_constant_values():
     check_output(got, jo.block_sparse_attention(qc, kc, vc, mask, lay), "given lists")
 
 
+@pytest.mark.parametrize("name", ["ragged_m128_d128", "ragged_m64_d128"])
+def test_lists_in_any_order_give_the_same_attention(name):
+    # Alg. 4 sums over a set of blocks: the order of the list must not matter beyond rounding
+    w = dict(CASES[name])
+    q, k, v = ji.make_qkv(w, 19)
+    layer = CarveLayer(w, "cuda:0")
+    lay = oracle_layout(w)
+    rng = np.random.default_rng(1)
+    mask = rng.random((w["batch"], w["heads"], lay.M, lay.M)) < 0.5
+    mask[:, :, np.arange(lay.M), np.arange(lay.M)] = True
+    cnt, idx = jo.mask_to_lists(mask)
+    for b in range(idx.shape[0]):
+        for h in range(idx.shape[1]):
+            for i in range(lay.M):
+                n = cnt[b, h, i]
+                idx[b, h, i, :n] = rng.permutation(idx[b, h, i, :n])
+    layer.permute_in(q.cuda(), k.cuda(), v.cuda())
+    layer.sel_count.copy_(torch.from_numpy(cnt))
+    layer.sel_index.copy_(torch.from_numpy(idx))
+    layer.attend()
+    torch.cuda.synchronize()
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    check_output(to_f64(layer.o_c), jo.block_sparse_attention(qc, kc, vc, mask, lay), "shuffled lists")
+
+
 def test_malformed_lists_do_not_fault():
     w = dict(CASES["tiny"])
     q, k, v = ji.make_qkv(w, 17)
