@@ -254,8 +254,8 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
     const bool valid = j < M;
     const bool eq = valid && key[t] == tau;
     const uint64_t eq_mask = __ballot(eq);
-    bool sel = (valid && key[t] > tau) || (eq && taken + __popcll(eq_mask & lt_mask) < need);
-    taken += __popcll(eq_mask);
+    bool sel = (valid && key[t] > tau) || (eq && taken + (int)__popcll(eq_mask & lt_mask) < need);
+    taken += (int)__popcll(eq_mask);
     if (t < nt64) sel = sel || ((fixed_bits[(size_t)i * nt64 + t] >> lane) & 1ull);
     sel = sel && valid;
     const uint64_t sel_mask = __ballot(sel);
