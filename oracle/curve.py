@@ -7,9 +7,19 @@ readable implementation.
 What it follows: Sec. 3.1, Eq. 2 of the paper defines the re-ordering G only as
 "an index permutation implemented via generalized Hilbert re-ordering" that
 works for cuboids whose sides are not powers of two (appendix, "Index Re-Order
-and Block Partition").  The paper prints no ordering, so the construction below
-is this build's own reading (equality with any third-party ordering: parity
-unpinned).  Everything downstream is defined relative to this order.
+and Block Partition"), and cites a published generalized-Hilbert ("gilbert")
+recursion for it.  The paper prints no ordering.  The construction below
+restates that published recursion from its description: the same case analysis
+(halve a long travel axis, a three-piece planar U when one side axis dominates,
+otherwise five pieces along the 8-cell Hilbert path, odd halves raised to even,
+line base cases, the planar rule).  What this build adds or chooses itself: the
+slab fallback to the planar rule when one length is 1, and the choice of the
+outermost travel axis (the longest side, ties w, h, t).  The cited source is not
+available here, so equality with its exact ordering is NOT claimed: parity
+unpinned.  What carries the curve in the tests are its properties (bijection,
+Chebyshev-1 continuity, the 2x2x2 Hilbert cell, the octant property), not
+agreement with the host C++ version, which is the same procedure written a
+second time.  Everything downstream is defined relative to this order.
 
 Construction.  box(p, A, B, C) visits every cell of the cuboid that has corner p
 and signed axis-aligned edge vectors A, B, C (lengths a, b, c >= 1).  It starts

@@ -237,19 +237,22 @@ def selection_margins(R, K_top, p):
 
 # --------------------------------------------------------------------------- Alg. 4 / Eq. 1
 
-def attention_block(q, k, v, mask_row, lay, i, beta=0.0):
+def attention_block(q, k, v, mask_row, lay, i, beta=0.0, return_lse=False):
     """Output rows of query block i of one (batch, head).
 
     q, k, v: float64 [N_pad, d] in curve order.  mask_row: bool [M].
     Keys: the valid tokens of the selected blocks.  Logit = q.k/sqrt(d), plus beta when
     the query block is a vision block and the key block is a text block (added after the
     scaling).  Pad query rows give zeros.  Returns [m, d].
+
+    return_lse: also return [m] with the natural-log sum of exp(logit) over the same keys
+    (the normaliser of Eq. 1 restricted to the visited set, Alg. 4's running l and m combined);
+    -inf for pad query rows and for rows without any key.
     """
     m, d = lay.m, q.shape[-1]
     out = np.zeros((m, d), dtype=np.float64)
+    lse = np.full(m, -np.inf)
     rows = np.nonzero(lay.valid[i * m:(i + 1) * m])[0]
-    if len(rows) == 0:
-        return out
     cols = []
     bias = []
     for j in np.nonzero(mask_row)[0]:
@@ -257,27 +260,37 @@ def attention_block(q, k, v, mask_row, lay, i, beta=0.0):
         cols.append(c)
         is_bias = (i < lay.M_v) and (j >= lay.M_v)
         bias.append(np.full(len(c), beta if is_bias else 0.0))
-    cols = np.concatenate(cols)
-    bias = np.concatenate(bias)
-    logits = q[rows + i * m] @ k[cols].T / math.sqrt(d) + bias[None, :]
-    logits -= logits.max(axis=1, keepdims=True)
-    P = np.exp(logits)
-    P /= P.sum(axis=1, keepdims=True)
-    out[rows] = P @ v[cols]
+    if len(rows) > 0 and len(cols) > 0:
+        cols = np.concatenate(cols)
+        bias = np.concatenate(bias)
+        logits = q[rows + i * m] @ k[cols].T / math.sqrt(d) + bias[None, :]
+        top = logits.max(axis=1, keepdims=True)
+        P = np.exp(logits - top)
+        denom = P.sum(axis=1, keepdims=True)
+        out[rows] = (P / denom) @ v[cols]
+        lse[rows] = top[:, 0] + np.log(denom[:, 0])
+    if return_lse:
+        return out, lse
     return out
 
 
-def block_sparse_attention(q, k, v, mask, lay, beta=0.0, only=None):
+def block_sparse_attention(q, k, v, mask, lay, beta=0.0, only=None, return_lse=False):
     """q, k, v float64 [B, heads, N_pad, d]; mask bool [B, heads, M, M] -> O like q.
 
     only: optional iterable of (b, h, i) to compute (other rows stay zero).
+    return_lse: also return the log-sum-exp of every row, [B, heads, N_pad] (see attention_block).
     """
     B, Hh, Np, D = q.shape
     out = np.zeros_like(q)
+    lse = np.full((B, Hh, Np), -np.inf)
     todo = only if only is not None else [(b, h, i) for b in range(B) for h in range(Hh) for i in range(lay.M)]
     m = lay.m
     for (b, h, i) in todo:
-        out[b, h, i * m:(i + 1) * m] = attention_block(q[b, h], k[b, h], v[b, h], mask[b, h, i], lay, i, beta)
+        o, l = attention_block(q[b, h], k[b, h], v[b, h], mask[b, h, i], lay, i, beta, return_lse=True)
+        out[b, h, i * m:(i + 1) * m] = o
+        lse[b, h, i * m:(i + 1) * m] = l
+    if return_lse:
+        return out, lse
     return out
 
 

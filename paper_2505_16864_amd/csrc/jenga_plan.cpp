@@ -4,8 +4,10 @@
 // on the resolution, so they are computed once per grid on the host (Alg. 1, "compute block
 // reordering and adjacency masks") and kept on the device inside the plan.
 //
-// The curve is this library's own generalized-Hilbert construction (the paper only names the
-// family).  A box with corner p and signed edge vectors A (travel axis), B, C is visited from p
+// The curve restates the published generalized-Hilbert recursion that Sec. 3.1 cites for Eq. 2 (the
+// paper only names it); the slab fallback and the choice of the outermost travel axis (longest
+// side, ties w, h, t) are this library's.  Equality with the cited project's exact ordering is not
+// claimed.  A box with corner p and signed edge vectors A (travel axis), B, C is visited from p
 // to the neighbouring corner along A:
 //   - two sides of length 1: a straight line;
 //   - one side of length 1: the planar rule in the other two axes;

@@ -143,3 +143,60 @@ def test_whole_layer_on_tiny_workload_matches_dense_when_all_selected():
     out2, mask2, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay2, w["p"])
     assert not mask2.all()
     assert np.abs(out2 - want).max() > 1e-6 and np.abs(out2 - want).mean() < np.abs(want).mean()
+
+
+def test_lse_against_explicit_loops_and_library_logsumexp():
+    # the normaliser of Eq. 1 over the visited keys: log sum exp(q.k/sqrt(d) + bias), natural log
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(8)
+    lay = jo.Layout(3, 5, 7, 40, 32, 0.3)        # ragged vision tail (9 valid) and ragged text tail (8 valid)
+    q, k, v = _inputs(rng, lay, heads=1)
+    qc, kc, vc = [jo.permute(x, lay) for x in (q, k, v)]
+    mask = rng.random((1, 1, lay.M, lay.M)) < 0.5
+    mask[0, 0, np.arange(lay.M), np.arange(lay.M)] = True
+    beta = 0.4
+    out, lse = jo.block_sparse_attention(qc, kc, vc, mask, lay, beta=beta, return_lse=True)
+    assert np.array_equal(out, jo.block_sparse_attention(qc, kc, vc, mask, lay, beta=beta))
+    m, d = lay.m, 8
+    for i in range(lay.M):
+        for r in range(i * m, (i + 1) * m):
+            if not lay.valid[r]:
+                assert lse[0, 0, r] == -np.inf
+                continue
+            logits = []
+            for j in np.nonzero(mask[0, 0, i])[0]:
+                for c in range(j * m, (j + 1) * m):
+                    if lay.valid[c]:
+                        s = sum(qc[0, 0, r, e] * kc[0, 0, c, e] for e in range(d)) / math.sqrt(d)
+                        logits.append(s + (beta if (i < lay.M_v and j >= lay.M_v) else 0.0))
+            assert lse[0, 0, r] == pytest.approx(logsumexp(np.array(logits)), abs=1e-12)
+            assert lse[0, 0, r] == pytest.approx(math.log(sum(math.exp(x) for x in logits)), abs=1e-12)
+
+
+def test_lse_merges_disjoint_key_sets():
+    # two disjoint visited sets A and B: lse(A u B) = log(e^lse(A) + e^lse(B)) and the outputs
+    # combine with those weights -- the identity that makes the value usable downstream
+    rng = np.random.default_rng(9)
+    lay = jo.Layout(2, 4, 4, 5, 8, 0.5)
+    q, k, v = _inputs(rng, lay, heads=2)
+    qc, kc, vc = [jo.permute(x, lay) for x in (q, k, v)]
+    full = np.ones((1, 2, lay.M, lay.M), dtype=bool)
+    a = np.zeros_like(full)
+    a[..., : lay.M // 2] = True
+    b = full & ~a
+    o, l = jo.block_sparse_attention(qc, kc, vc, full, lay, return_lse=True)
+    oa, la = jo.block_sparse_attention(qc, kc, vc, a, lay, return_lse=True)
+    ob, lb = jo.block_sparse_attention(qc, kc, vc, b, lay, return_lse=True)
+    ok = lay.valid
+    assert np.allclose(l[:, :, ok], np.logaddexp(la[:, :, ok], lb[:, :, ok]), atol=1e-12)
+    wa = np.exp(la[:, :, ok] - l[:, :, ok])[..., None]
+    wb = np.exp(lb[:, :, ok] - l[:, :, ok])[..., None]
+    assert np.allclose(o[:, :, ok], wa * oa[:, :, ok] + wb * ob[:, :, ok], atol=1e-12)
+    # one key with logit exactly 0 (zero query): lse = log(number of keys)
+    z = np.zeros_like(qc)
+    _, l0 = jo.block_sparse_attention(z, kc, vc, full, lay, return_lse=True)
+    assert np.allclose(l0[:, :, ok], math.log(ok.sum()), atol=1e-14)
+    # a row list that is empty gives -inf and a zero row
+    none = np.zeros_like(full)
+    o_n, l_n = jo.block_sparse_attention(qc, kc, vc, none, lay, return_lse=True)
+    assert not o_n.any() and np.isneginf(l_n).all()

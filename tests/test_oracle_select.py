@@ -155,3 +155,29 @@ def test_mask_to_lists():
     cnt, idx = jo.mask_to_lists(mask)
     assert cnt.tolist() == [[[2, 1, 3]]]
     assert idx[0, 0, 0, :2].tolist() == [0, 2] and idx[0, 0, 1, 0] == 1 and idx[0, 0, 2].tolist() == [0, 1, 2]
+
+
+def test_selection_margins_on_hand_worked_rows():
+    # dyadic rows: the sorted values, their running sums and therefore both margins are exact
+    # row A: sorted .5 .25 .125 .0625 .0625, C = .5 .75 .875 .9375 1
+    rA = np.array([0.5, 0.125, 0.25, 0.0625, 0.0625])
+    R = rA[None, None, None, :]
+    # K_top 1, p .6: n* = 2 -> N_k = 2; gap between 2nd (.25) and 3rd (.125) = .5 of .25; nearest C to p: .5 (|.1|)
+    gap, c = jo.selection_margins(R, 1, 0.6)
+    assert gap == 0.5 and c == pytest.approx(0.1, abs=1e-15)
+    # K_top 3, p .25: N_k = 3; gap (.125 - .0625)/.125 = .5; |C - p| smallest at C_1 = .5 -> .25
+    gap, c = jo.selection_margins(R, 3, 0.25)
+    assert gap == 0.5 and c == 0.25
+    # K_top 4: the 4th and 5th sorted values are equal -> zero gap (a tie the inputs must avoid)
+    gap, c = jo.selection_margins(R, 4, 0.25)
+    assert gap == 0.0
+    # p exactly on a running sum -> zero distance (C_2 = .75)
+    gap, c = jo.selection_margins(R, 1, 0.75)
+    assert c == 0.0 and gap == 0.5             # n* = #{C <= .75} + 1 = 3, gap between .125 and .0625
+    # every block kept: no gap to report
+    gap, c = jo.selection_margins(R, 5, 0.0)
+    assert gap == np.inf and c == 0.5
+    # the minimum is taken over rows: add a row with a smaller gap
+    rB = np.array([0.5, 0.25, 0.1875, 0.0625, 0.0])   # K_top 2: (.25 - .1875)/.25 = .25
+    gap, c = jo.selection_margins(np.stack([rA, rB])[None, None], 2, 0.0)
+    assert gap == 0.25 and c == 0.5
