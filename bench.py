@@ -86,8 +86,15 @@ def stage_switch_bench(dev, reps=20):
 
 def sustained_mfma_tflops(dev, seconds=0.15):
     """What the matrix cores sustain on random bf16 operands under the power limit (MFMA-only loop)."""
+    import ctypes
     import torch
-    from paper_2505_16864_amd import binding as jb
+    lib_path = os.path.join(ROOT, "bench_mfma_probe.so")
+    if not os.path.exists(lib_path):
+        return None
+    probe = ctypes.CDLL(lib_path).bench_mfma_probe
+    probe.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                      ctypes.c_int32, ctypes.c_void_p]
+    probe.restype = ctypes.c_int
     g = torch.Generator().manual_seed(99)
     ops = torch.randn(65536, generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
     n_wg = 2 * torch.cuda.get_device_properties(0).multi_processor_count     # two waves per SIMD
@@ -97,7 +104,8 @@ def sustained_mfma_tflops(dev, seconds=0.15):
     iters, rate = 20000, 0.0
     for _ in range(3):            # calibrate the length, then measure a run of about `seconds`
         a.record()
-        jb.jenga_mfma_probe(ops, sink, iters, n_wg, stream)
+        if probe(ops.data_ptr(), ops.numel() * 2, sink.data_ptr(), sink.numel(), iters, n_wg, stream) != 0:
+            return None
         b.record()
         torch.cuda.synchronize()
         ms = a.elapsed_time(b)
@@ -196,8 +204,9 @@ def main():
                      "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
     }
     sustained = sustained_mfma_tflops(dev)
-    out["roofline"]["mfma_only_random_operands_tflops"] = sustained
-    out["roofline"]["frac_of_mfma_only"] = attn_tflops / sustained
+    if sustained:
+        out["roofline"]["mfma_only_random_operands_tflops"] = sustained
+        out["roofline"]["frac_of_mfma_only"] = attn_tflops / sustained
     out["stage_switch"] = stage_switch_bench(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v)

@@ -1,9 +1,17 @@
-// Measurement aid, not part of the method: a resident loop of independent bf16 MFMAs on operands the
-// caller supplies.  With random operands it shows what the matrix cores of this part sustain under
-// their power limit, the second denominator bench.py prints beside the nominal peak.
+// Measurement aid of bench.py, not part of the library or of the method: a resident loop of
+// independent bf16 MFMAs on operands the caller supplies.  With random operands it shows what the
+// matrix cores of this part sustain under their power limit, the second denominator bench.py prints
+// beside the nominal peak.  Built into its own shared object (bench_mfma_probe.so) next to bench.py.
+//
+//   operands_bf16 : device, >= 65,536 bytes of bf16 values, 16-byte aligned, read only
+//   sink          : device, >= n_workgroups * 256 floats, overwritten
+//   iters         : even, >= 2;  n_workgroups in [1, 65536]
+// Runs n_workgroups x 4 wavefronts, each issuing 4 * iters independent v_mfma_f32_32x32x16_bf16
+// (32,768 FLOP each).  Returns 0, or -1 on bad arguments, -4 when the launch fails; only enqueues.
 #include <hip/hip_runtime.h>
 
-#include "jenga_internal.h"
+#include <cstddef>
+#include <cstdint>
 
 namespace {
 
@@ -41,12 +49,12 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict
 
 }  // namespace
 
-extern "C" int jenga_mfma_probe(const void* operands_bf16, size_t operand_bytes, float* sink, size_t sink_floats,
+extern "C" int bench_mfma_probe(const void* operands_bf16, size_t operand_bytes, float* sink, size_t sink_floats,
                                 int32_t iters, int32_t n_workgroups, void* stream) {
-  if (!operands_bf16 || !sink) return JENGA_EINVAL;
-  if (iters < 2 || (iters & 1) || n_workgroups < 1 || n_workgroups > 65536) return JENGA_EINVAL;
-  if (operand_bytes < 65536 || sink_floats < (size_t)n_workgroups * 256) return JENGA_EWORKSPACE;
-  if (((uintptr_t)operands_bf16 & 15u) != 0) return JENGA_EINVAL;
+  if (!operands_bf16 || !sink) return -1;
+  if (iters < 2 || (iters & 1) || n_workgroups < 1 || n_workgroups > 65536) return -1;
+  if (operand_bytes < 65536 || sink_floats < (size_t)n_workgroups * 256) return -1;
+  if (((uintptr_t)operands_bf16 & 15u) != 0) return -1;
   mfma_probe_kernel<<<dim3(n_workgroups), 256, 0, (hipStream_t)stream>>>((const u32x4*)operands_bf16, sink, iters);
-  return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
+  return hipGetLastError() == hipSuccess ? 0 : -4;
 }

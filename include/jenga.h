@@ -23,7 +23,8 @@
  *     only enqueue work: no allocation, no host synchronisation, no host<->device copies.
  *   - Every function returns JENGA_OK (0) or a negative jenga_status; nothing is thrown across
  *     the ABI and nothing is launched when validation fails.
- *   - One GPU: a plan belongs to the device that was current when it was created.
+ *   - One GPU: a plan belongs to the device that was current when it was created; a call that uses
+ *     the plan's device tables with another device current returns JENGA_EINVAL.
  */
 #ifndef JENGA_H_
 #define JENGA_H_
@@ -61,7 +62,8 @@ typedef struct {
   double topk_ratio;   /* k in (0, 1]: keep at least K_top = max(1, floor(k*M_v + 1e-6)) blocks */
   double cum_prob;     /* p in [0, 1): extend until the kept probability mass exceeds p         */
   float text_bias;     /* beta of the text-attention amplifier (Sec. 3.2), added to the scaled
-                          logits of vision-query x text-key pairs; 0 switches it off           */
+                          logits of vision-query x text-key pairs; 0 switches it off; must be
+                          finite (NaN or +-inf: JENGA_EINVAL)                                  */
   uint32_t flags;      /* JENGA_FLAG_*                                                         */
 } jenga_config;
 
@@ -156,13 +158,18 @@ int jenga_select_blocks(const jenga_plan* plan, const void* q_curve, const void*
  *                out of range; a count of 0 gives zero rows.  The order of a list does not matter
  *                beyond rounding (any permutation of the same blocks is accepted)
  *   out_curve  : bf16 curve side, fully overwritten
+ *   lse_or_null: float32 [batch][heads][N_pad] or NULL.  For every valid query row the natural
+ *                logarithm of the sum of exp(logit) over the keys it visited (logits scaled and
+ *                biased as above): Alg. 4's running maximum and running sum combined, the value a
+ *                caller needs to merge this result with attention over other keys.  Pad query rows
+ *                and rows of an empty list get -inf.  Fully overwritten when given
  *   workspace  : at least attn_workspace_bytes, 256-byte aligned (K and V re-tiled for the
  *                matrix cores), contents undefined after
  * Equivalent to jenga_pack_kv followed by jenga_block_sparse_attn_packed on the same workspace.
  */
 int jenga_block_sparse_attn(const jenga_plan* plan, const void* q, const void* k, const void* v,
                             const int32_t* sel_count, const int32_t* sel_index, void* out_curve,
-                            void* workspace, size_t workspace_bytes, void* stream);
+                            float* lse_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * First half of jenga_block_sparse_attn: re-tiles K and V of every block (Alg. 4's "load key-value
@@ -178,7 +185,8 @@ int jenga_pack_kv(const jenga_plan* plan, const void* k, const void* v, void* wo
  */
 int jenga_block_sparse_attn_packed(const jenga_plan* plan, const void* q, const void* packed_kv_workspace,
                                    size_t workspace_bytes, const int32_t* sel_count,
-                                   const int32_t* sel_index, void* out_curve, void* stream);
+                                   const int32_t* sel_index, void* out_curve, float* lse_or_null,
+                                   void* stream);
 
 /*
  * Eq. 2, z_thw = G^-1(z_blk): dst_thw[b][src(i)][h][:] = src_curve[b][h][i][:] for every valid
@@ -205,20 +213,6 @@ int jenga_unpermute(const jenga_plan* plan, const void* src_curve, void* dst_thw
 int jenga_stage_switch(const float* x_t, const float* eps_t, const float* eps_tilde, float* x_out,
                        int32_t channels, int32_t T_in, int32_t H_in, int32_t W_in, int32_t T_out,
                        int32_t H_out, int32_t W_out, float sigma_t, void* stream);
-
-/*
- * Measurement aid (no passage of the paper: it is the "MFMA-only" yardstick of the benchmark): runs
- * n_workgroups x 4 wavefronts, each issuing 4 * iters independent v_mfma_f32_32x32x16_bf16 (32,768 FLOP
- * each) on fragments taken from `operands_bf16`, and writes one float per thread to `sink` so that the
- * work is not optimised away.  The caller times it; with random operands and >= 100 ms of work the rate
- * is what the matrix cores sustain under the part's power limit.
- *   operands_bf16 : device, >= 65,536 bytes of bf16 values, 16-byte aligned, read only
- *   sink          : device, >= n_workgroups * 256 floats, overwritten
- *   iters         : even, >= 2;  n_workgroups in [1, 65536]
- * JENGA_EINVAL / JENGA_EWORKSPACE on bad arguments; only enqueues work on `stream`.
- */
-int jenga_mfma_probe(const void* operands_bf16, size_t operand_bytes, float* sink, size_t sink_floats,
-                     int32_t iters, int32_t n_workgroups, void* stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char* jenga_strerror(int status);

@@ -32,6 +32,13 @@ WORKLOADS = {
     "hy720p_k10":  dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.10, p=0.3),
     "wan480p_p90": dict(T=21, H=30, W=52, n_text=512, batch=1, heads=40, head_dim=128, block=128, topk=0.30, p=0.9),
     "hy720p_k20":  dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.20, p=0.3),
+    # Wan2.1-1.3B's own latent grid (appendix, detailed parameters) with the cumulative-probability cut the paper
+    # uses for Wan; the head count (12 x 128) is an assumption, the paper does not state it
+    "wan13b":      dict(T=20, H=30, W=52, n_text=512, batch=1, heads=12, head_dim=128, block=128, topk=0.30, p=0.9),
+    # the low-resolution ProRes stage with the text-attention amplifier on (rho = 0.5, 0.75x stage: beta =
+    # -0.5 log 0.5625); same tensors as hy_lowres
+    "hy_lowres_amp": dict(T=33, H=24, W=42, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3,
+                          text_bias=0.2876820724517809),
     # the largest block count the library takes (M = 2048): 2032 vision blocks of 32 tokens + 16 text blocks
     "max_blocks": {"T": 8, "H": 64, "W": 127, "n_text": 512, "batch": 1, "heads": 2, "head_dim": 64, "block": 32,
                    "topk": 0.05, "p": 0.3},

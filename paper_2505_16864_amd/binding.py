@@ -15,8 +15,7 @@ JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
            "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
-           "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch", "jenga_mfma_probe",
-           "jenga_strerror"]
+           "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch", "jenga_strerror"]
 
 
 class jenga_config(ctypes.Structure):
@@ -53,11 +52,10 @@ def _load():
     lib.jenga_unpermute.argtypes = [vp, vp, vp, vp]
     lib.jenga_curve_permute_rows.argtypes = [vp, vp, vp, ctypes.c_int32, vp]
     lib.jenga_select_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
-    lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
-    lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp]
+    lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp, vp]
     lib.jenga_stage_switch.argtypes = [vp, vp, vp, vp] + [ctypes.c_int32] * 7 + [ctypes.c_float, vp]
-    lib.jenga_mfma_probe.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, vp]
     lib.jenga_strerror.argtypes = [ctypes.c_int]
     lib.jenga_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -137,10 +135,11 @@ def jenga_select_blocks(plan, q_curve, k_curve, sel_count, sel_index, mask, work
                                     _ptr(mask), _ptr(workspace), workspace_bytes, stream), "jenga_select_blocks")
 
 
-def jenga_block_sparse_attn(plan, q, k, v, sel_count, sel_index, out_curve, workspace, workspace_bytes,
+def jenga_block_sparse_attn(plan, q, k, v, sel_count, sel_index, out_curve, lse, workspace, workspace_bytes,
                             stream=None):
+    """lse: float32 device tensor [batch, heads, N_pad] or None."""
     _check(_lib.jenga_block_sparse_attn(plan, _ptr(q), _ptr(k), _ptr(v), _ptr(sel_count), _ptr(sel_index),
-                                        _ptr(out_curve), _ptr(workspace), workspace_bytes, stream),
+                                        _ptr(out_curve), _ptr(lse), _ptr(workspace), workspace_bytes, stream),
            "jenga_block_sparse_attn")
 
 
@@ -148,10 +147,10 @@ def jenga_pack_kv(plan, k, v, workspace, workspace_bytes, stream=None):
     _check(_lib.jenga_pack_kv(plan, _ptr(k), _ptr(v), _ptr(workspace), workspace_bytes, stream), "jenga_pack_kv")
 
 
-def jenga_block_sparse_attn_packed(plan, q, workspace, workspace_bytes, sel_count, sel_index, out_curve,
+def jenga_block_sparse_attn_packed(plan, q, workspace, workspace_bytes, sel_count, sel_index, out_curve, lse=None,
                                    stream=None):
     _check(_lib.jenga_block_sparse_attn_packed(plan, _ptr(q), _ptr(workspace), workspace_bytes, _ptr(sel_count),
-                                               _ptr(sel_index), _ptr(out_curve), stream),
+                                               _ptr(sel_index), _ptr(out_curve), _ptr(lse), stream),
            "jenga_block_sparse_attn_packed")
 
 
@@ -160,12 +159,6 @@ def jenga_stage_switch(x_t, eps_t, eps_tilde, x_out, channels, in_shape, out_sha
     _check(_lib.jenga_stage_switch(_ptr(x_t), _ptr(eps_t), _ptr(eps_tilde), _ptr(x_out), channels,
                                    *[int(v) for v in in_shape], *[int(v) for v in out_shape], float(sigma_t), stream),
            "jenga_stage_switch")
-
-
-def jenga_mfma_probe(operands_bf16, sink, iters, n_workgroups, stream=None):
-    """operands_bf16: device bf16 tensor of >= 32768 elements; sink: device float32 tensor of >= n_workgroups*256."""
-    _check(_lib.jenga_mfma_probe(_ptr(operands_bf16), operands_bf16.numel() * operands_bf16.element_size(),
-                                 _ptr(sink), sink.numel(), iters, n_workgroups, stream), "jenga_mfma_probe")
 
 
 def raw():

@@ -6,7 +6,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libjenga.so")
-SOURCES = ["jenga_plan.cpp", "jenga_permute.hip", "jenga_select.hip", "jenga_attn.hip", "jenga_prores.hip", "jenga_probe.hip", "jenga_capi.hip"]
+SOURCES = ["jenga_plan.cpp", "jenga_permute.hip", "jenga_select.hip", "jenga_attn.hip", "jenga_prores.hip", "jenga_capi.hip"]
 
 
 def build_library(verbose=False):
@@ -26,5 +26,19 @@ def build_library(verbose=False):
     return LIB
 
 
+def build_bench_probe():
+    """bench.py's MFMA-only yardstick: its own shared object beside bench.py, not part of the library."""
+    src = os.path.join(ROOT, "bench_mfma_probe.hip")
+    out = os.path.join(ROOT, "bench_mfma_probe.so")
+    cmd = ["hipcc", "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", src, "-o", out]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stderr)
+        raise RuntimeError("hipcc failed building bench_mfma_probe.so")
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_bench_probe())

@@ -163,9 +163,8 @@ template <int BLK, int D>
 __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MIN_WAVES)) void attn_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
-    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int n_bh, int M, int M_v, int n_pad,
-    int chunk,
-    float scale_log2e, float bias_log2e) {
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, float* __restrict__ lse, int n_bh, int M,
+    int M_v, int n_pad, int chunk, float scale_log2e, float bias_log2e) {
   using TR = AttnTraits<BLK, D>;
   constexpr int NTHR = TR::NTHR, MT = TR::MT, KS = TR::KS, DT = TR::DT, PS = TR::PS;
   constexpr int TILE_CHUNKS = TR::TILE_CHUNKS, CPT = TR::CPT;
@@ -291,6 +290,9 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const bool row_ok = (32 * wave + ql) < blk_valid[i] && l_tot > 0.f;
   const float inv = row_ok ? 1.0f / l_tot : 0.f;
+  // natural-log sum of exp(logit) over the visited keys: the running maximum is in base-2 units
+  if (lse != nullptr && hl == 0)
+    lse[(size_t)bh * n_pad + qrow] = row_ok ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   uint16_t* orow = out + ((size_t)bh * n_pad + qrow) * D;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -348,8 +350,8 @@ template <int D>
 __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
-    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, int n_bh, int M, int M_v, int n_pad,
-    int chunk, int pad_v, int pad_c, float scale_log2e, float bias_log2e) {
+    const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, float* __restrict__ lse, int n_bh, int M,
+    int M_v, int n_pad, int chunk, int pad_v, int pad_c, float scale_log2e, float bias_log2e) {
   constexpr int BLK = 128, KS = D / 16, DT = D / 32, PS = BLK / 16, MH = 2, PH = 4;
   constexpr int TILE_CHUNKS = BLK * D / 8, HALF_CHUNKS = TILE_CHUNKS / 2, CPT = HALF_CHUNKS / 256;
   __shared__ u32x4 Ks[HALF_CHUNKS];   // fragments (m2, ks) of the current 64 keys
@@ -525,6 +527,9 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   const bool row_ok = (32 * wave + ql) < blk_valid[i] && l_tot > 0.f;
   const float inv = row_ok ? 1.0f / l_tot : 0.f;
+  // natural-log sum of exp(logit) over the visited keys: the running maximum is in base-2 units
+  if (lse != nullptr && hl == 0)
+    lse[(size_t)bh * n_pad + qrow] = row_ok ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   uint16_t* orow = out + ((size_t)bh * n_pad + qrow) * D;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -552,7 +557,7 @@ int run_pack(const jenga_plan* p, const void* k, const void* v, void* ws, hipStr
 
 template <int BLK, int D>
 int run_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
-                  const int32_t* sel_index, void* out, hipStream_t st) {
+                  const int32_t* sel_index, void* out, float* lse, hipStream_t st) {
   const jenga_config& c = p->cfg;
   const jenga_plan_info_t& f = p->info;
   const int bh = c.batch * c.heads;
@@ -565,12 +570,12 @@ int run_attention(const jenga_plan* p, const void* q, const void* ws, const int3
   const float scale = log2e / sqrtf((float)D);
   if constexpr (BLK == 128)
     attn_h_kernel<D><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
-                                                          p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
-                                                          chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e);
+                                                          p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v,
+                                                          f.N_pad, chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e);
   else
     attn_kernel<BLK, D><<<dim3(n_wg), AttnTraits<BLK, D>::NTHR, 0, st>>>(
-        (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, bh, f.M, f.M_v, f.N_pad,
-        chunk, scale, c.text_bias * log2e);
+        (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v,
+        f.N_pad, chunk, scale, c.text_bias * log2e);
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
 
@@ -591,11 +596,11 @@ int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, voi
 }
 
 int launch_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
-                     const int32_t* sel_index, void* out, void* stream) {
+                     const int32_t* sel_index, void* out, float* lse, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int blk = p->cfg.block, d = p->cfg.head_dim;
 #define X(B, DD) \
-  if (blk == B && d == DD) return run_attention<B, DD>(p, q, ws, sel_count, sel_index, out, st);
+  if (blk == B && d == DD) return run_attention<B, DD>(p, q, ws, sel_count, sel_index, out, lse, st);
   JENGA_FOR_SHAPES(X)
 #undef X
   return JENGA_EUNSUPPORTED;

@@ -1,6 +1,7 @@
 // The C ABI (see include/jenga.h): argument validation, plan life cycle, dispatch to the launchers.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -13,7 +14,7 @@ bool config_ok(const jenga_config& c, int* why) {
   if (c.T < 1 || c.H < 1 || c.W < 1 || c.n_text < 0 || c.batch < 1 || c.heads < 1) return false;
   if (!(c.topk_ratio > 0.0 && c.topk_ratio <= 1.0)) return false;
   if (!(c.cum_prob >= 0.0 && c.cum_prob < 1.0)) return false;
-  if (!(c.text_bias == c.text_bias)) return false;
+  if (!std::isfinite(c.text_bias)) return false;   // NaN and +-inf: exp2(-inf + inf) would poison a row
   if (c.flags & ~7u) return false;
   *why = JENGA_EUNSUPPORTED;
   if (c.head_dim != 64 && c.head_dim != 128) return false;
@@ -24,6 +25,13 @@ bool config_ok(const jenga_config& c, int* why) {
   if (M > 2048) return false;   // select keeps a row of M block probabilities in one wavefront
   if ((long long)c.batch * c.heads > 65535) return false;
   return true;
+}
+
+// The plan's tables live on the device that was current at creation; a hot call made with another
+// device current would launch there with pointers that device cannot read.
+bool on_plan_device(const jenga_plan* p) {
+  int dev = -1;
+  return hipGetDevice(&dev) == hipSuccess && dev == p->device;
 }
 
 template <typename T>
@@ -128,18 +136,21 @@ int jenga_plan_tables(const jenga_config* cfg, jenga_plan_info_t* info, int32_t*
 
 int jenga_curve_permute(const jenga_plan* p, const void* src_thw, void* dst_curve, void* stream) {
   if (!p || !src_thw || !dst_curve) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   return jenga::launch_permute(p, src_thw, dst_curve, true, stream);
 }
 
 int jenga_curve_permute_rows(const jenga_plan* p, const void* src_rows, void* dst_rows, int32_t row_bytes,
                              void* stream) {
   if (!p || !src_rows || !dst_rows) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   if (row_bytes < 16 || row_bytes > 4096 || (row_bytes & (row_bytes - 1)) != 0) return JENGA_EUNSUPPORTED;
   return jenga::launch_permute_rows(p, src_rows, dst_rows, row_bytes, stream);
 }
 
 int jenga_unpermute(const jenga_plan* p, const void* src_curve, void* dst_thw, void* stream) {
   if (!p || !src_curve || !dst_thw) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   return jenga::launch_permute(p, src_curve, dst_thw, false, stream);
 }
 
@@ -147,25 +158,28 @@ int jenga_select_blocks(const jenga_plan* p, const void* q_curve, const void* k_
                         int32_t* sel_index, uint8_t* mask_or_null, void* workspace, size_t workspace_bytes,
                         void* stream) {
   if (!p || !q_curve || !k_curve || !sel_count || !sel_index || !workspace) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   if (((uintptr_t)workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.select_workspace_bytes) return JENGA_EWORKSPACE;
   return jenga::launch_select(p, q_curve, k_curve, sel_count, sel_index, mask_or_null, workspace, stream);
 }
 
 int jenga_block_sparse_attn(const jenga_plan* p, const void* q, const void* k, const void* v,
-                            const int32_t* sel_count, const int32_t* sel_index, void* out_curve, void* workspace,
-                            size_t workspace_bytes, void* stream) {
+                            const int32_t* sel_count, const int32_t* sel_index, void* out_curve,
+                            float* lse_or_null, void* workspace, size_t workspace_bytes, void* stream) {
   if (!p || !q || !k || !v || !sel_count || !sel_index || !out_curve || !workspace) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   if (((uintptr_t)workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
   const int rc = jenga::launch_pack(p, k, v, workspace, stream);
   if (rc != JENGA_OK) return rc;
-  return jenga::launch_attention(p, q, workspace, sel_count, sel_index, out_curve, stream);
+  return jenga::launch_attention(p, q, workspace, sel_count, sel_index, out_curve, lse_or_null, stream);
 }
 
 int jenga_pack_kv(const jenga_plan* p, const void* k, const void* v, void* workspace, size_t workspace_bytes,
                   void* stream) {
   if (!p || !k || !v || !workspace) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   if (((uintptr_t)workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
   return jenga::launch_pack(p, k, v, workspace, stream);
@@ -173,11 +187,12 @@ int jenga_pack_kv(const jenga_plan* p, const void* k, const void* v, void* works
 
 int jenga_block_sparse_attn_packed(const jenga_plan* p, const void* q, const void* packed_kv_workspace,
                                    size_t workspace_bytes, const int32_t* sel_count, const int32_t* sel_index,
-                                   void* out_curve, void* stream) {
+                                   void* out_curve, float* lse_or_null, void* stream) {
   if (!p || !q || !packed_kv_workspace || !sel_count || !sel_index || !out_curve) return JENGA_EINVAL;
+  if (!on_plan_device(p)) return JENGA_EINVAL;
   if (((uintptr_t)packed_kv_workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
-  return jenga::launch_attention(p, q, packed_kv_workspace, sel_count, sel_index, out_curve, stream);
+  return jenga::launch_attention(p, q, packed_kv_workspace, sel_count, sel_index, out_curve, lse_or_null, stream);
 }
 
 const char* jenga_strerror(int status) {

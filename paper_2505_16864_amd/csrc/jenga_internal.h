@@ -36,6 +36,6 @@ int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* se
                   int32_t* sel_index, uint8_t* mask, void* ws, void* stream);
 int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, void* stream);
 int launch_attention(const jenga_plan* p, const void* q, const void* packed_ws, const int32_t* sel_count,
-                     const int32_t* sel_index, void* out, void* stream);
+                     const int32_t* sel_index, void* out, float* lse, void* stream);
 
 }  // namespace jenga

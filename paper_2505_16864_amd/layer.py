@@ -8,8 +8,10 @@ class CarveLayer:
     """Allocates the curve-side tensors, index lists and workspaces of one configuration once and
     runs the four calls on torch's current stream."""
 
-    def __init__(self, w, device="cuda:0", text_bias=0.0, flags=7, want_mask=False):
+    def __init__(self, w, device="cuda:0", text_bias=None, flags=7, want_mask=False, want_lse=False):
         self.w = dict(w)
+        if text_bias is None:
+            text_bias = w.get("text_bias", 0.0)
         self.device = torch.device(device)
         self.cfg = B.make_config(w["T"], w["H"], w["W"], w["n_text"], w["batch"], w["heads"], w["head_dim"],
                                  w["block"], w["topk"], w["p"], text_bias, flags)
@@ -23,6 +25,7 @@ class CarveLayer:
         self.sel_count = torch.empty((w["batch"], w["heads"], i.M), dtype=torch.int32, device=dev)
         self.sel_index = torch.full((w["batch"], w["heads"], i.M, i.M), -1, dtype=torch.int32, device=dev)
         self.mask = torch.zeros((w["batch"], w["heads"], i.M, i.M), dtype=torch.uint8, device=dev) if want_mask else None
+        self.lse = torch.empty((w["batch"], w["heads"], i.N_pad), dtype=torch.float32, device=dev) if want_lse else None
         self.ws_select = torch.empty(max(1, i.select_workspace_bytes), dtype=torch.uint8, device=dev)
         self.ws_attn = torch.empty(max(1, i.attn_workspace_bytes), dtype=torch.uint8, device=dev)
         self.out_thw = torch.empty((w["batch"], i.N_v + w["n_text"], w["heads"], w["head_dim"]),
@@ -43,14 +46,14 @@ class CarveLayer:
 
     def attend(self):
         B.jenga_block_sparse_attn(self.plan, self.q_c, self.k_c, self.v_c, self.sel_count, self.sel_index,
-                                  self.o_c, self.ws_attn, self.ws_attn.numel(), self._stream())
+                                  self.o_c, self.lse, self.ws_attn, self.ws_attn.numel(), self._stream())
 
     def pack(self):
         B.jenga_pack_kv(self.plan, self.k_c, self.v_c, self.ws_attn, self.ws_attn.numel(), self._stream())
 
     def attend_packed(self):
         B.jenga_block_sparse_attn_packed(self.plan, self.q_c, self.ws_attn, self.ws_attn.numel(), self.sel_count,
-                                         self.sel_index, self.o_c, self._stream())
+                                         self.sel_index, self.o_c, self.lse, self._stream())
 
     def permute_out(self):
         B.jenga_unpermute(self.plan, self.o_c, self.out_thw, self._stream())

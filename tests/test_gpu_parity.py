@@ -1,6 +1,8 @@
 """GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded
 inputs.  Permutation, masks and index lists bit-exact; attention within max-abs 2e-2 and 1e-2 of the
 largest reference magnitude per head."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -29,13 +31,15 @@ CASES = {
 }
 
 
-def _run(name, seed=11, flags=7, text_bias=0.0, w_override=None):
+def _run(name, seed=11, flags=7, text_bias=0.0, w_override=None, want_lse=False):
     w = dict(CASES[name])
     if w_override:
         w.update(w_override)
-    print("case", name, "seed", seed, "flags", flags, flush=True)
+    print("case", name, "seed", seed, "flags", flags, "text_bias", text_bias, flush=True)
     q, k, v = ji.make_qkv(w, seed)
-    layer = CarveLayer(w, "cuda:0", text_bias=text_bias, flags=flags, want_mask=True)
+    layer = CarveLayer(w, "cuda:0", text_bias=text_bias, flags=flags, want_mask=True, want_lse=want_lse)
+    layer.o_c.view(torch.int16).fill_(0x7FC1)            # NaN pattern: every row must be overwritten
+    layer.out_thw.view(torch.int16).fill_(0x7FC1)
     out = layer.forward(q.cuda(), k.cuda(), v.cuda())
     torch.cuda.synchronize()
     lay = oracle_layout(w, flags)
@@ -119,14 +123,71 @@ def test_all_blocks_selected_equals_dense_attention():
     check_output(to_f64(out).transpose(0, 2, 1, 3), want.transpose(0, 2, 1, 3), "dense")
 
 
-def test_text_bias():
-    import math
-    beta = -0.5 * math.log(0.5625)
-    w, (q, k, v), layer, out, lay = _run("ragged_m32_d64", seed=15, text_bias=beta)
-    want_out, want_mask, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"], beta=beta)
+# The text-attention amplifier (Sec. 3.2; the highlighted lines of Alg. 4) on every kernel shape.  The 128-token
+# cases run the half-block kernel the paper's configurations use: ragged_m128_d128 has a last vision block with
+# 51 valid tokens (its second half is all padding) and a ragged text block; m128_d64 has a text block with 33
+# valid tokens (second half all padding); small has 64 text tokens (again an all-padding half) and no vision pads.
+@pytest.mark.parametrize("beta", [-0.5 * math.log(0.5625), -1.5, 3.0])
+@pytest.mark.parametrize("name", ["ragged_m32_d64", "ragged_m64_d128", "ragged_m128_d128", "m128_d64", "small"])
+def test_text_bias(name, beta):
+    w, (q, k, v), layer, out, lay = _run(name, seed=15, text_bias=beta)
+    want_out, want_mask, want_oc = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"], beta=beta)
     base_out, _, _ = jo.carve_layer(ji.bits(q), ji.bits(k), ji.bits(v), lay, w["p"], beta=0.0)
-    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), "text bias")
-    assert np.abs(want_out - base_out).max() > 5e-2      # the bias is visible at this tolerance
+    assert np.array_equal(layer.mask.cpu().numpy().astype(bool), want_mask)      # the bias plays no part in selection
+    check_output(to_f64(layer.o_c), want_oc, "%s text bias %.3f curve side" % (name, beta))
+    check_output(to_f64(out).transpose(0, 2, 1, 3), want_out.transpose(0, 2, 1, 3), "%s text bias %.3f" % (name, beta))
+    assert not ji.bits(layer.o_c)[:, :, ~lay.valid].any()
+    assert np.abs(want_out - base_out).max() > 2e-2      # the bias is visible at this tolerance
+
+
+def test_text_bias_with_the_ragged_blocks_visited_first():
+    # shuffled lists put the ragged vision block (second half all padding) and the ragged text block at the
+    # front of some rows, so the running maximum starts from them
+    beta = -0.5 * math.log(0.5625)
+    w = dict(CASES["ragged_m128_d128"])
+    q, k, v = ji.make_qkv(w, 21)
+    layer = CarveLayer(w, "cuda:0", text_bias=beta)
+    lay = oracle_layout(w)
+    rng = np.random.default_rng(2)
+    mask = rng.random((w["batch"], w["heads"], lay.M, lay.M)) < 0.5
+    mask[:, :, :, lay.M_v - 1] = True
+    mask[:, :, :, lay.M - 1] = True
+    cnt, idx = jo.mask_to_lists(mask)
+    for h in range(idx.shape[1]):
+        for i in range(lay.M):
+            n = cnt[0, h, i]
+            rest = [j for j in idx[0, h, i, :n] if j not in (lay.M_v - 1, lay.M - 1)]
+            first = [lay.M_v - 1, lay.M - 1] if i % 2 == 0 else [lay.M - 1, lay.M_v - 1]
+            idx[0, h, i, :n] = first + list(rng.permutation(rest))
+    layer.permute_in(q.cuda(), k.cuda(), v.cuda())
+    layer.sel_count.copy_(torch.from_numpy(cnt))
+    layer.sel_index.copy_(torch.from_numpy(idx))
+    layer.o_c.view(torch.int16).fill_(0x7FC1)
+    layer.attend()
+    torch.cuda.synchronize()
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    check_output(to_f64(layer.o_c), jo.block_sparse_attention(qc, kc, vc, mask, lay, beta=beta), "ragged first")
+
+
+# Log-sum-exp output: natural log of the sum of exp(logit) over the visited keys, -inf for pad rows.  float32
+# online softmax in base 2 against the float64 oracle: 1e-3 absolute.
+@pytest.mark.parametrize("name,beta", [("tiny", 0.0), ("small", 0.0), ("ragged_m32_d64", 0.3), ("ragged_m64_d128", 0.0),
+                                       ("ragged_m128_d128", -0.5 * math.log(0.5625)), ("m128_d64", 0.0),
+                                       ("one_token_each", 0.0), ("single_block", 0.0)])
+def test_log_sum_exp(name, beta):
+    w, (q, k, v), layer, out, lay = _run(name, seed=22, text_bias=beta, want_lse=True)
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    mask = jo.build_mask(qc, kc, lay, w["p"])
+    want_o, want_lse = jo.block_sparse_attention(qc, kc, vc, mask, lay, beta=beta, return_lse=True)
+    got = layer.lse.cpu().numpy().astype(np.float64)
+    assert np.isneginf(got[:, :, ~lay.valid]).all()
+    assert np.abs(got[:, :, lay.valid] - want_lse[:, :, lay.valid]).max() <= 1e-3
+    check_output(to_f64(layer.o_c), want_o, name + " with lse")
+    # an empty list gives -inf
+    layer.sel_count.zero_()
+    layer.attend()
+    torch.cuda.synchronize()
+    assert np.isneginf(layer.lse.cpu().numpy()).all()
 
 
 def test_attention_with_given_lists_and_constant_values():
@@ -202,7 +263,7 @@ def test_workspace_and_alignment_errors():
     assert e.value.status == -3
     with pytest.raises(J.JengaError) as e:
         J.jenga_block_sparse_attn(layer.plan, layer.q_c, layer.k_c, layer.v_c, layer.sel_count, layer.sel_index,
-                                  layer.o_c, layer.ws_attn.data_ptr() + 16, layer.info.attn_workspace_bytes)
+                                  layer.o_c, None, layer.ws_attn.data_ptr() + 16, layer.info.attn_workspace_bytes)
     assert e.value.status == -1
 
 

@@ -86,7 +86,9 @@ def test_k_top_and_workspace_sizes():
 @pytest.mark.parametrize("bad,status", [
     (dict(T=0), -1), (dict(n_text=-1), -1), (dict(batch=0), -1), (dict(heads=0), -1),
     (dict(topk=0.0), -1), (dict(topk=1.5), -1), (dict(p=1.0), -1), (dict(p=-0.1), -1), (dict(flags=8), -1),
-    (dict(text_bias=float("nan")), -1),
+    (dict(text_bias=float("nan")), -1), (dict(text_bias=float("inf")), -1), (dict(text_bias=float("-inf")), -1),
+    # Alg. 2's text-only branch (no vision tokens) is plain dense attention and is not taken by this library
+    (dict(T=0, H=0, W=0), -1), (dict(W=0), -1),
     (dict(head_dim=96), -2), (dict(block=16), -2), (dict(block=256), -2), (dict(T=400, H=400, W=400), -2),
 ])
 def test_invalid_configs_are_rejected(bad, status):
@@ -111,9 +113,8 @@ def test_null_arguments_return_einval_without_a_device():
     assert lib.jenga_unpermute(None, None, None, None) == -1
     assert lib.jenga_curve_permute_rows(None, None, None, 512, None) == -1
     assert lib.jenga_select_blocks(None, None, None, None, None, None, None, 0, None) == -1
-    assert lib.jenga_block_sparse_attn(None, None, None, None, None, None, None, None, 0, None) == -1
+    assert lib.jenga_block_sparse_attn(None, None, None, None, None, None, None, None, None, 0, None) == -1
     assert lib.jenga_pack_kv(None, None, None, None, 0, None) == -1
-    assert lib.jenga_block_sparse_attn_packed(None, None, None, 0, None, None, None, None) == -1
+    assert lib.jenga_block_sparse_attn_packed(None, None, None, 0, None, None, None, None, None) == -1
     assert lib.jenga_stage_switch(None, None, None, None, 1, 1, 1, 1, 1, 1, 1, 0.5, None) == -1
-    assert lib.jenga_mfma_probe(None, 0, None, 0, 2, 1, None) == -1
     assert lib.jenga_plan_destroy(None) == 0
