@@ -6,7 +6,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libjenga.so")
-SOURCES = ["jenga_plan.cpp", "jenga_permute.hip", "jenga_select.hip", "jenga_attn.hip", "jenga_prores.hip", "jenga_capi.hip"]
+SOURCES = ["jenga_plan.cpp", "jenga_host.cpp", "jenga_permute.hip", "jenga_select.hip", "jenga_attn.hip", "jenga_prores.hip", "jenga_capi.hip"]
 
 
 def build_library(verbose=False):

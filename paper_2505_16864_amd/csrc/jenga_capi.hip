@@ -1,31 +1,13 @@
-// The C ABI (see include/jenga.h): argument validation, plan life cycle, dispatch to the launchers.
+// The device half of the C ABI (see include/jenga.h): plan life cycle on the device, argument validation of
+// the hot calls, dispatch to the launchers.  The host-only entry points live in jenga_host.cpp.
 #include <hip/hip_runtime.h>
 
-#include <cmath>
 #include <cstring>
 #include <new>
 
 #include "jenga_internal.h"
 
 namespace {
-
-bool config_ok(const jenga_config& c, int* why) {
-  *why = JENGA_EINVAL;
-  if (c.T < 1 || c.H < 1 || c.W < 1 || c.n_text < 0 || c.batch < 1 || c.heads < 1) return false;
-  if (!(c.topk_ratio > 0.0 && c.topk_ratio <= 1.0)) return false;
-  if (!(c.cum_prob >= 0.0 && c.cum_prob < 1.0)) return false;
-  if (!std::isfinite(c.text_bias)) return false;   // NaN and +-inf: exp2(-inf + inf) would poison a row
-  if (c.flags & ~7u) return false;
-  *why = JENGA_EUNSUPPORTED;
-  if (c.head_dim != 64 && c.head_dim != 128) return false;
-  if (c.block != 32 && c.block != 64 && c.block != 128) return false;
-  const long long nv = (long long)c.T * c.H * c.W;
-  if (nv > (1ll << 24) || c.n_text > (1 << 20)) return false;
-  const long long M = (nv + c.block - 1) / c.block + (c.n_text + c.block - 1) / c.block;
-  if (M > 2048) return false;   // select keeps a row of M block probabilities in one wavefront
-  if ((long long)c.batch * c.heads > 65535) return false;
-  return true;
-}
 
 // The plan's tables live on the device that was current at creation; a hot call made with another
 // device current would launch there with pointers that device cannot read.
@@ -52,7 +34,7 @@ int jenga_plan_create(const jenga_config* cfg, jenga_plan** out) {
   if (!cfg || !out) return JENGA_EINVAL;
   *out = nullptr;
   int why;
-  if (!config_ok(*cfg, &why)) return why;
+  if (!jenga::config_ok(*cfg, &why)) return why;
   jenga_plan* p = new (std::nothrow) jenga_plan();
   if (!p) return JENGA_ENOMEM;
   p->cfg = *cfg;
@@ -83,53 +65,6 @@ int jenga_plan_destroy(jenga_plan* p) {
   if (p->d_src_of_pos && hipFree(p->d_src_of_pos) != hipSuccess) rc = JENGA_EHIP;
   if (p->d_blk_valid && hipFree(p->d_blk_valid) != hipSuccess) rc = JENGA_EHIP;
   if (p->d_fixed_bits && hipFree(p->d_fixed_bits) != hipSuccess) rc = JENGA_EHIP;
-  delete p;
-  return rc;
-}
-
-int jenga_plan_info(const jenga_plan* p, jenga_plan_info_t* info) {
-  if (!p || !info) return JENGA_EINVAL;
-  *info = p->info;
-  return JENGA_OK;
-}
-
-int jenga_plan_export(const jenga_plan* p, int32_t* perm, int32_t* inv_perm, uint8_t* adja) {
-  if (!p) return JENGA_EINVAL;
-  const size_t nv = (size_t)p->info.N_v;
-  if (perm) std::memcpy(perm, p->perm.data(), nv * sizeof(int32_t));
-  if (inv_perm) std::memcpy(inv_perm, p->inv_perm.data(), nv * sizeof(int32_t));
-  if (adja) {
-    const int mv = p->info.M_v;
-    const bool on = (p->cfg.flags & JENGA_FLAG_ADJACENCY) != 0;
-    for (int i = 0; i < mv; ++i)
-      for (int j = 0; j < mv; ++j)
-        adja[(size_t)i * mv + j] =
-            on ? (uint8_t)((p->fixed_bits[(size_t)i * p->nt64 + (j >> 6)] >> (j & 63)) & 1ull) : 0;
-  }
-  return JENGA_OK;
-}
-
-int jenga_plan_tables(const jenga_config* cfg, jenga_plan_info_t* info, int32_t* perm, int32_t* inv_perm,
-                      uint8_t* adja) {
-  if (!cfg || !info) return JENGA_EINVAL;
-  int why;
-  if (!config_ok(*cfg, &why)) return why;
-  jenga_plan* p = new (std::nothrow) jenga_plan();
-  if (!p) return JENGA_ENOMEM;
-  p->cfg = *cfg;
-  p->d_src_of_pos = nullptr;
-  p->d_blk_valid = nullptr;
-  p->d_fixed_bits = nullptr;
-  int rc = JENGA_OK;
-  try {
-    rc = jenga::build_host_tables(p);
-  } catch (const std::bad_alloc&) {
-    rc = JENGA_ENOMEM;
-  }
-  if (rc == JENGA_OK) {
-    *info = p->info;
-    rc = jenga_plan_export(p, perm, inv_perm, adja);
-  }
   delete p;
   return rc;
 }
@@ -193,18 +128,6 @@ int jenga_block_sparse_attn_packed(const jenga_plan* p, const void* q, const voi
   if (((uintptr_t)packed_kv_workspace & 255u) != 0) return JENGA_EINVAL;
   if (workspace_bytes < p->info.attn_workspace_bytes) return JENGA_EWORKSPACE;
   return jenga::launch_attention(p, q, packed_kv_workspace, sel_count, sel_index, out_curve, lse_or_null, stream);
-}
-
-const char* jenga_strerror(int status) {
-  switch (status) {
-    case JENGA_OK: return "ok";
-    case JENGA_EINVAL: return "invalid argument";
-    case JENGA_EUNSUPPORTED: return "configuration not supported by this build";
-    case JENGA_EWORKSPACE: return "workspace too small";
-    case JENGA_EHIP: return "HIP runtime or kernel launch failure";
-    case JENGA_ENOMEM: return "out of memory";
-    default: return "unknown status";
-  }
 }
 
 }  // extern "C"

@@ -23,6 +23,9 @@ struct jenga_plan {
 
 namespace jenga {
 
+// Validates a configuration; on failure *why is the jenga_status to return.
+bool config_ok(const jenga_config& c, int* why);
+
 // Curve order of a T x H x W grid: fills cells with the thw index of each curve position.
 void curve_order(int T, int H, int W, bool use_curve, std::vector<int32_t>& perm);
 
