@@ -147,6 +147,21 @@ int jenga_select_blocks(const jenga_plan* plan, const void* q_curve, const void*
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * jenga_select_blocks for callers that cannot allocate or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same computation, same outputs, same kernels; the
+ * workspace is a static device array of JENGA_SELECT_STATIC_MAX_BYTES inside the library (one per GPU, resident
+ * from module load until the process ends).  The call allocates nothing and frees nothing.
+ *   - JENGA_EWORKSPACE when the plan's select_workspace_bytes exceeds JENGA_SELECT_STATIC_MAX_BYTES
+ *     (nothing is launched); JENGA_EINVAL for null pointers or when the current device is not the plan's.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different
+ *     streams, different threads) race on it and must be serialised by the caller.  The array keeps the
+ *     last call's contents; the kernels overwrite everything they read, so no clearing is needed.
+ */
+#define JENGA_SELECT_STATIC_MAX_BYTES (64u << 20)
+int jenga_select_blocks_static(const jenga_plan* plan, const void* q_curve, const void* k_curve,
+                               int32_t* sel_count, int32_t* sel_index, uint8_t* mask_or_null, void* stream);
+
+/*
  * Alg. 4 (and Alg. 2's dense rows for text queries, which simply carry a full index list).
  * For query block i of (batch, head): softmax attention of its valid rows over the valid keys of
  * the blocks sel_index[..][i][0 .. sel_count), logits q.k/sqrt(d_k) (+ text_bias for a vision

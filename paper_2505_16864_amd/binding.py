@@ -14,7 +14,8 @@ JENGA_FLAG_CONDITION = 2
 JENGA_FLAG_CURVE = 4
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
-           "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_block_sparse_attn", "jenga_pack_kv",
+           "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_select_blocks_static",
+           "jenga_block_sparse_attn", "jenga_pack_kv",
            "jenga_block_sparse_attn_packed", "jenga_unpermute", "jenga_stage_switch", "jenga_strerror"]
 
 
@@ -52,6 +53,7 @@ def _load():
     lib.jenga_unpermute.argtypes = [vp, vp, vp, vp]
     lib.jenga_curve_permute_rows.argtypes = [vp, vp, vp, ctypes.c_int32, vp]
     lib.jenga_select_blocks.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.jenga_select_blocks_static.argtypes = [vp, vp, vp, vp, vp, vp, vp]
     lib.jenga_block_sparse_attn.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_pack_kv.argtypes = [vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.jenga_block_sparse_attn_packed.argtypes = [vp, vp, vp, ctypes.c_size_t, vp, vp, vp, vp, vp]
@@ -133,6 +135,11 @@ def jenga_select_blocks(plan, q_curve, k_curve, sel_count, sel_index, mask, work
                         stream=None):
     _check(_lib.jenga_select_blocks(plan, _ptr(q_curve), _ptr(k_curve), _ptr(sel_count), _ptr(sel_index),
                                     _ptr(mask), _ptr(workspace), workspace_bytes, stream), "jenga_select_blocks")
+
+
+def jenga_select_blocks_static(plan, q_curve, k_curve, sel_count, sel_index, mask, stream=None):
+    _check(_lib.jenga_select_blocks_static(plan, _ptr(q_curve), _ptr(k_curve), _ptr(sel_count), _ptr(sel_index),
+                                           _ptr(mask), stream), "jenga_select_blocks_static")
 
 
 def jenga_block_sparse_attn(plan, q, k, v, sel_count, sel_index, out_curve, lse, workspace, workspace_bytes,

@@ -48,6 +48,7 @@ int jenga_plan_create(const jenga_config* cfg, jenga_plan** out) {
     rc = JENGA_ENOMEM;
   }
   if (rc == JENGA_OK && hipGetDevice(&p->device) != hipSuccess) rc = JENGA_EHIP;
+  if (rc == JENGA_OK) rc = jenga::select_scratch_init(p->device);
   if (rc == JENGA_OK) rc = to_device(p->src_of_pos, &p->d_src_of_pos);
   if (rc == JENGA_OK) rc = to_device(p->blk_valid, &p->d_blk_valid);
   if (rc == JENGA_OK) rc = to_device(p->fixed_bits, &p->d_fixed_bits);

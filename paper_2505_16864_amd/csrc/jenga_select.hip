@@ -14,8 +14,13 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "jenga_internal.h"
+
+// Workspace of jenga_select_blocks_static: one copy per GPU, held from module load to process end.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)JENGA_SELECT_STATIC_MAX_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -299,9 +304,31 @@ int run_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_c
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
 
+// ---- scratch of the allocation-free entry point ------------------------------------------------
+// One array per GPU, resident from module load until the process ends.  The name below is only a
+// host-side handle: device code and HIP calls get the address hipGetSymbolAddress returns for the
+// device that is current, looked up once per device and kept here.
+constexpr int MAX_DEVICES = 64;
+void* scratch_of_device[MAX_DEVICES] = {};
+std::mutex scratch_lock;
+
+// Address of `scratch` on `device`, which must be the current device; nullptr on failure.
+void* scratch_address(int device) {
+  if (device < 0 || device >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> guard(scratch_lock);
+  if (scratch_of_device[device] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    scratch_of_device[device] = ptr;
+  }
+  return scratch_of_device[device];
+}
+
 }  // namespace
 
 namespace jenga {
+
+int select_scratch_init(int device) { return scratch_address(device) != nullptr ? JENGA_OK : JENGA_EHIP; }
 
 int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* sel_count, int32_t* sel_index,
                   uint8_t* mask, void* ws, void* stream) {
@@ -311,3 +338,17 @@ int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* se
 }
 
 }  // namespace jenga
+
+extern "C" int jenga_select_blocks_static(const jenga_plan* p, const void* q_curve, const void* k_curve,
+                                          int32_t* sel_count, int32_t* sel_index, uint8_t* mask_or_null,
+                                          void* stream) {
+  if (!p || !q_curve || !k_curve || !sel_count || !sel_index) return JENGA_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != p->device) return JENGA_EINVAL;
+  if (p->info.select_workspace_bytes > STATIC_SCRATCH_BYTES) return JENGA_EWORKSPACE;
+  void* ws = scratch_address(dev);   // looked up when the plan was created; never allocates
+  if (ws == nullptr) return JENGA_EHIP;
+  // every byte of the scratch that select_kernel reads is written first by pool_kernel and
+  // scores_kernel of this same call, so nothing has to be cleared between calls
+  return jenga::launch_select(p, q_curve, k_curve, sel_count, sel_index, mask_or_null, ws, stream);
+}
