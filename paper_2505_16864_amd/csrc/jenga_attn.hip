@@ -116,12 +116,27 @@ __device__ inline void tile_to_lds(const u32x4* __restrict__ src_tile, u32x4* ld
 
 __device__ inline void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0) only
 
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-
-// acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16)
-__device__ inline float dot2_ones(uint32_t packed_pair, float acc) {
-  const bf16x2v ones = {(__bf16)1.0f, (__bf16)1.0f};
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, packed_pair), ones, acc, false);
+// Online-softmax bookkeeping with a lazily moved reference (Alg. 4 keeps a running maximum m and
+// rescales l and O whenever it grows).  Here the reference m_run only moves when some row's new
+// maximum exceeds it by more than LAZY_LOG2 (in base-2 logit units): until then the probabilities are
+// formed against the old reference and stay below 2^LAZY_LOG2, which the float32 sums and the bf16
+// products hold without loss (bf16 has float32's exponent range), and the final division by l
+// cancels the common factor exactly as it does for the running maximum.  The branch is uniform over
+// the wavefront; after the first few blocks it is almost never taken.
+constexpr float LAZY_LOG2 = 8.0f;
+template <int DT>
+__device__ __forceinline__ void rescale_if_grown(float cand, float& m_run, float& l_run, f32x16 (&O)[DT]) {
+  if (__ballot(cand > m_run + LAZY_LOG2)) {   // also taken by the first block with a valid key (m_run = -inf)
+    asm volatile("");                         // keep it a real branch
+    const float m_new = fmaxf(m_run, cand);
+    const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+    l_run *= alpha;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+  }
 }
 
 // Work mapping shared by the attention kernels.  The text query blocks of every (batch, head) are
@@ -241,10 +256,9 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[mt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
-    const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    const float off = bias - m_new;
-    float rs = 0.f;
+    rescale_if_grown(fmaf(mx, scale_log2e, bias), m_run, l_run, O);
+    const float off = m_run == -INFINITY ? 0.f : bias - m_run;   // every key so far was padding: keep it finite
+    float rs0 = 0.f, rs1 = 0.f;
     bf16x8 pb[PS];
 #pragma unroll
     for (int ps = 0; ps < PS; ++ps) {
@@ -254,20 +268,13 @@ __global__ __launch_bounds__((AttnTraits<BLK, D>::NTHR), (AttnTraits<BLK, D>::MI
         const float p0 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2], scale_log2e, off));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(S[ps >> 1][8 * (ps & 1) + 2 * e2 + 1], scale_log2e, off));
         w[e2] = pack_bf16x2(p0, p1);
-        rs = dot2_ones(w[e2], rs);   // row sum of the rounded P that PV multiplies
+        rs0 += p0;
+        rs1 += p1;
       }
       u32x4 pw = {w[0], w[1], w[2], w[3]};
       pb[ps] = __builtin_bit_cast(bf16x8, pw);
     }
-    l_run = fmaf(l_run, alpha, rs);
-    m_run = m_new;
-    if (__ballot(alpha != 1.0f)) {
-      asm volatile("");
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-    }
+    l_run += rs0 + rs1;
 
     wait_vmem();       // this wave's part of the V tile has landed
     __syncthreads();   // V tile is in LDS; every wave is done reading the K tile
@@ -465,11 +472,9 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[m2][r]);
     mx = max_with_other_half(mx);
     const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
-    // a half block whose keys are all padding has mx = -inf; keep the arithmetic finite
-    const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
-    const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
-    const float off = m_new == -INFINITY ? 0.f : bias - m_new;
-    float rs = 0.f;
+    rescale_if_grown(fmaf(mx, scale_log2e, bias), m_run, l_run, O);
+    const float off = m_run == -INFINITY ? 0.f : bias - m_run;   // every key so far was padding: keep it finite
+    float rs0 = 0.f, rs1 = 0.f;
     bf16x8 pb[PH];
 #pragma unroll
     for (int p2 = 0; p2 < PH; ++p2) {
@@ -479,20 +484,13 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
         const float p0 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2], scale_log2e, off));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2 + 1], scale_log2e, off));
         w[e2] = pack_bf16x2(p0, p1);
-        rs = dot2_ones(w[e2], rs);
+        rs0 += p0;
+        rs1 += p1;
       }
       u32x4 pw = {w[0], w[1], w[2], w[3]};
       pb[p2] = __builtin_bit_cast(bf16x8, pw);
     }
-    l_run = fmaf(l_run, alpha, rs);
-    m_run = m_new;
-    if (__ballot(alpha != 1.0f)) {
-      asm volatile("");
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
-    }
+    l_run += rs0 + rs1;
 
     wait_vmem();       // this wave's part of the V half has landed
     __syncthreads();   // V half is in LDS; every wave is done reading the K half
