@@ -62,6 +62,78 @@ def cpu_baseline(w, q, k, v, seconds_budget=20.0):
             "measured_s": t_select_head + t_attn}
 
 
+class Telemetry:
+    """Samples the package power and the shader clocks with `amd-smi metric -p -c` (read-only) in a thread while
+    a block of work runs; reports what the part held under that load.  Absent tool or parse failure: None."""
+
+    def __init__(self, period=0.25):
+        import threading
+        self.period, self.samples, self._stop = period, [], False
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import subprocess
+        while not self._stop:
+            try:
+                r = subprocess.run(["amd-smi", "metric", "-p", "-c"], capture_output=True, text=True, timeout=10)
+                power, clocks, in_gfx = None, [], False
+                for line in r.stdout.splitlines():
+                    t = line.strip()
+                    if t.startswith("SOCKET_POWER"):
+                        power = float(t.split(":")[1].split()[0])
+                    elif t.startswith("GFX_"):
+                        in_gfx = True
+                    elif in_gfx and t.startswith("CLK:"):
+                        clocks.append(float(t.split(":")[1].split()[0]))
+                        in_gfx = False
+                if power is not None and clocks:
+                    self.samples.append((time.time(), power, sum(clocks) / len(clocks)))
+            except Exception:
+                return
+            time.sleep(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop = True
+        self._thread.join(timeout=15)
+
+    def summary(self, t_from, t_to):
+        inside = [(p, c) for (t, p, c) in self.samples if t_from <= t <= t_to]
+        if not inside:
+            return None
+        return {"samples": len(inside), "socket_power_w": sum(p for p, _ in inside) / len(inside),
+                "gfx_clock_mhz": sum(c for _, c in inside) / len(inside)}
+
+
+def attention_under_load(layer, seconds=4.0):
+    """Runs the attention kernel back to back for about `seconds` and samples power and clock meanwhile: the
+    clock the part holds under this kernel (it runs at the package power limit) is what the percentage of the
+    nominal peak has to be read against."""
+    import torch
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    layer.attend_packed()
+    b.record()
+    torch.cuda.synchronize()
+    reps = max(4, int(seconds * 1e3 / max(a.elapsed_time(b), 1e-3)))
+    with Telemetry() as tel:
+        time.sleep(0.3)
+        t0 = time.time()
+        a.record()
+        for _ in range(reps):
+            layer.attend_packed()
+        b.record()
+        torch.cuda.synchronize()
+        t1 = time.time()
+    out = tel.summary(t0 + 1.0, t1)      # skip the ramp at the start
+    if out is not None:
+        out["attn_ms_back_to_back"] = a.elapsed_time(b) / reps
+    return out
+
+
 def stage_switch_bench(dev, reps=20):
     """The resolution switch between stages (Eq. 4) at the 540p -> 720p latent shape: HBM-bound, beside the layer."""
     import torch
@@ -122,6 +194,10 @@ def main():
     ap.add_argument("--workload", default="hy720p")
     ap.add_argument("--seed", type=int, default=5000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-telemetry", action="store_true", help="skip the power/clock sampling run")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="attribution run: the lists are selected on the real inputs, then Q, K, V are zeroed before "
+                         "the attention is timed (same work, no data-dependent switching power)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists)")
@@ -153,6 +229,12 @@ def main():
         marks[1].record()
         layer.select()
         marks[2].record()
+        if args.zero_operands:
+            layer.q_c.zero_()
+            layer.k_c.zero_()
+            layer.v_c.zero_()
+            torch.cuda.synchronize()
+            marks[2].record()
         layer.pack()
         marks[3].record()
         layer.attend_packed()
@@ -179,10 +261,19 @@ def main():
     tensor_bytes = 2.0 * (info.N_v + w["n_text"]) * heads * d * batch
     permute_gbs = 2 * tensor_bytes * 4 / ((ms["permute_in"] + ms["permute_out"]) * 1e-3) / 1e9
 
-    traffic = None
+    # algorithmic bytes of the HBM-bound stages: pooling reads Q and K once, the index lists are written once;
+    # packing reads K and V and writes both re-tiled
+    n_pad_bytes = 2.0 * info.N_pad * heads * d * batch
+    select_gbs = (2 * n_pad_bytes + 4.0 * sel_total) / (ms["select"] * 1e-3) / 1e9
+    pack_gbs = 4 * n_pad_bytes / (ms["pack"] * 1e-3) / 1e9
+
+    # HBM-side traffic of the attention kernel comes from rocprofv3 counters, which cannot be read from inside this
+    # process: the figure of the committed profile of this workload is quoted, with its source
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_traffic.json" % args.workload)
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        traffic_source = "profiles/" + os.path.basename(tpath) + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 
     out = {
         "metric": "ms per block-sparse attention layer (select + attention)",
@@ -199,14 +290,19 @@ def main():
         "executed_tflops": attn_tflops, "dense_equiv_tflops": dense_flop / (ms["attn"] * 1e-3) / 1e12,
         "layer_executed_tflops": executed_flop / (layer_ms * 1e-3) / 1e12,
         "density": density, "mean_selected_blocks": sel_total / float(batch * heads * info.M),
-        "permute_gbs": permute_gbs,
+        "permute_gbs": permute_gbs, "select_gbs": select_gbs, "pack_gbs": pack_gbs,
         "roofline": {"kernel": "attn_h_kernel<128>" if m == 128 else "attn_kernel", "bound": "mfma", "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic},
+                     "unit": "TFLOP/s", "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_source": traffic_source},
     }
     sustained = sustained_mfma_tflops(dev)
     if sustained:
         out["roofline"]["mfma_only_random_operands_tflops"] = sustained
         out["roofline"]["frac_of_mfma_only"] = attn_tflops / sustained
+    if args.zero_operands:
+        out["data"] = "synthetic; lists from the real inputs, attention timed on all-zero Q, K, V (attribution run)"
+    if not args.no_telemetry:
+        out["under_load"] = attention_under_load(layer)
     out["stage_switch"] = stage_switch_bench(dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, q, k, v)
