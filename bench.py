@@ -193,6 +193,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="hy720p")
     ap.add_argument("--seed", type=int, default=5000)
+    ap.add_argument("--walk", choices=["paced", "ordered"], default="paced",
+                    help="order in which the attention kernel visits the selected blocks: paced by a chip-wide clock "
+                         "(library flag JENGA_FLAG_PACED_WALK, the faster one) or in list order (bit-reproducible)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-telemetry", action="store_true", help="skip the power/clock sampling run")
     ap.add_argument("--zero-operands", action="store_true",
@@ -204,6 +207,7 @@ def main():
 
     import torch
     import jenga_inputs as ji
+    from paper_2505_16864_amd import binding as B
     from paper_2505_16864_amd.layer import CarveLayer
 
     if not torch.cuda.is_available():
@@ -211,7 +215,8 @@ def main():
     w = ji.WORKLOADS[args.workload]
     dev = "cuda:0"
     q, k, v = ji.make_qkv(w, args.seed, device=dev)
-    layer = CarveLayer(w, dev)
+    flags = (w.get("flags", 7) & 7) | (8 if args.walk == "paced" else 0)
+    layer = CarveLayer(w, dev, flags=flags)
     info = layer.info
 
     def ev():
@@ -282,7 +287,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "grid": [w["T"], w["H"], w["W"]], "n_text": w["n_text"],
                    "heads": heads, "head_dim": d, "block": m, "topk": w["topk"], "p": w["p"],
-                   "tokens_padded": info.N_pad, "blocks": info.M, "seed": args.seed},
+                   "tokens_padded": info.N_pad, "blocks": info.M, "seed": args.seed, "walk": args.walk},
         "ms": ms,
         "ms_median": {n: sorted(samples[n])[len(samples[n]) // 2] for n in names},
         "ms_min": {n: min(samples[n]) for n in names},
@@ -299,6 +304,19 @@ def main():
     if sustained:
         out["roofline"]["mfma_only_random_operands_tflops"] = sustained
         out["roofline"]["frac_of_mfma_only"] = attn_tflops / sustained
+    # the other walk of the same kernel on the same lists and tiles, for comparison (a few launches)
+    other = CarveLayer(w, dev, flags=flags ^ 8)
+    a, b = ev(), ev()
+    times = []
+    for _ in range(4):
+        a.record()
+        B.jenga_block_sparse_attn_packed(other.plan, layer.q_c, layer.ws_attn, layer.ws_attn.numel(), layer.sel_count,
+                                         layer.sel_index, layer.o_c, None, torch.cuda.current_stream().cuda_stream)
+        b.record()
+        torch.cuda.synchronize()
+        times.append(a.elapsed_time(b))
+    out["attn_ms_other_walk"] = {"walk": "ordered" if args.walk == "paced" else "paced", "ms": sum(times[1:]) / 3}
+    del other
     if args.zero_operands:
         out["data"] = "synthetic; lists from the real inputs, attention timed on all-zero Q, K, V (attribution run)"
     if not args.no_telemetry:

@@ -48,7 +48,12 @@ typedef enum {
 enum {
   JENGA_FLAG_ADJACENCY = 1u, /* union with B_adja (Sec. 3.1 item 3)                          */
   JENGA_FLAG_CONDITION = 2u, /* union with B_cond: all text key blocks (Sec. 3.1 item 2)      */
-  JENGA_FLAG_CURVE = 4u      /* 1: generalized Hilbert order; 0: linear thw order (ablation)  */
+  JENGA_FLAG_CURVE = 4u,     /* 1: generalized Hilbert order; 0: linear thw order (ablation)  */
+  JENGA_FLAG_PACED_WALK = 8u /* attention with blocks of 128 tokens visits the selected key blocks in an
+                                order paced by a chip-wide clock instead of list order, so that the
+                                workgroups of an XCD share tiles in the L2 (Alg. 4 sums over a set: the
+                                order is free).  Faster; the last bits of the output may differ between
+                                runs; a block listed twice is visited once.  Ignored for other block sizes */
 };
 
 /* Problem statement of one layer (Sec. 3.1; Alg. 2 and Alg. 3 inputs). */
@@ -179,7 +184,7 @@ int jenga_select_blocks_static(const jenga_plan* plan, const void* q_curve, cons
  *                caller needs to merge this result with attention over other keys.  Pad query rows
  *                and rows of an empty list get -inf.  Fully overwritten when given
  *   workspace  : at least attn_workspace_bytes, 256-byte aligned (K and V re-tiled for the
- *                matrix cores), contents undefined after
+ *                matrix cores, and 256 bytes of launch parameters), contents undefined after
  * Equivalent to jenga_pack_kv followed by jenga_block_sparse_attn_packed on the same workspace.
  */
 int jenga_block_sparse_attn(const jenga_plan* plan, const void* q, const void* k, const void* v,
@@ -196,9 +201,10 @@ int jenga_pack_kv(const jenga_plan* plan, const void* k, const void* v, void* wo
 
 /*
  * Second half of jenga_block_sparse_attn: the block-sparse attention kernel itself, reading K and V
- * from a workspace filled by jenga_pack_kv for the same plan.  Other arguments as above.
+ * from a workspace filled by jenga_pack_kv for the same plan.  The packed tiles are only read; the last
+ * 256 bytes of the workspace (launch parameters) may be written.  Other arguments as above.
  */
-int jenga_block_sparse_attn_packed(const jenga_plan* plan, const void* q, const void* packed_kv_workspace,
+int jenga_block_sparse_attn_packed(const jenga_plan* plan, const void* q, void* packed_kv_workspace,
                                    size_t workspace_bytes, const int32_t* sel_count,
                                    const int32_t* sel_index, void* out_curve, float* lse_or_null,
                                    void* stream);

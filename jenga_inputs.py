@@ -39,6 +39,9 @@ WORKLOADS = {
     # -0.5 log 0.5625); same tensors as hy_lowres
     "hy_lowres_amp": dict(T=33, H=24, W=42, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3,
                           text_bias=0.2876820724517809),
+    # the headline layer with the time-paced walk of the attention kernel (flag bit 3 of the library)
+    "hy720p_paced": dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3,
+                         flags=15),
     # the largest block count the library takes (M = 2048): 2032 vision blocks of 32 tokens + 16 text blocks
     "max_blocks": {"T": 8, "H": 64, "W": 127, "n_text": 512, "batch": 1, "heads": 2, "head_dim": 64, "block": 32,
                    "topk": 0.05, "p": 0.3},

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(PKG, "libjenga.so")
 JENGA_FLAG_ADJACENCY = 1
 JENGA_FLAG_CONDITION = 2
 JENGA_FLAG_CURVE = 4
+JENGA_FLAG_PACED_WALK = 8
 
 EXPORTS = ["jenga_plan_create", "jenga_plan_destroy", "jenga_plan_info", "jenga_plan_export", "jenga_plan_tables",
            "jenga_curve_permute", "jenga_curve_permute_rows", "jenga_select_blocks", "jenga_select_blocks_static",

@@ -4,7 +4,8 @@
 // One workgroup owns one query block of BLK rows of one (batch, head): BLK/32 wavefronts, each with
 // 32 query rows.  It walks the ascending list of selected key blocks.  Per key block:
 //     S^T = K Q^T         v_mfma_f32_32x32x16_bf16, K fragments from LDS, Q fragments in registers
-//     online softmax      float32, base-2 exponent, statistics per query row
+//     online softmax      float32, base-2 exponent, statistics per query row; the reference maximum
+//                         moves lazily (rescale_if_grown), row sums are float32 sums of P
 //     O^T += V^T P^T      v_mfma_f32_32x32x16_bf16, V^T fragments from LDS, P^T straight from the
 //                         S^T accumulators
 // Working on the transposed products keeps one query row in one lane (column) of every
@@ -325,6 +326,13 @@ __device__ __forceinline__ void static_for(F&& f) {
 // One 1 KB MFMA fragment (16 bytes per lane) from LDS, issued here and now: the compiler's own
 // scheduling reads one fragment, waits, multiplies, and so leaves the LDS latency open before
 // every MFMA.  Reads issued through lds_frag are complete only after lds_wait on their registers.
+// Between the two asm statements the destination registers are in flight: the code is correct only
+// as long as the compiler does not copy or reuse them there.  lds_wait ties them ("+v") so that the
+// allocator has no reason to, and tests/test_kernel_listing.py checks the generated listing of every
+// build for exactly this (no instruction between a read and its wait touches the read's registers).
+// Folding read, MFMAs and wait of a group into one asm statement removes the assumption but was
+// measured 4 % slower here: with S live the register budget of three wavefronts per SIMD only leaves
+// room for groups of two, and the compiler can no longer lay the softmax arithmetic under the MFMAs.
 template <int BYTE_OFF>
 __device__ __forceinline__ void lds_frag(u32x4& dst, uint32_t lane_addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(lane_addr), "n"(BYTE_OFF) : "memory");
@@ -352,17 +360,29 @@ __device__ inline float max_with_other_half(float x) {
 // the S and P registers and half the LDS of a step over 128, which lets three workgroups (twelve
 // wavefronts) live on a CU instead of two; everything else is attn_kernel: 4 waves x 32 query
 // rows, transposed products, K and V^T fragments straight from the packed tiles, DMA to LDS.
+//
+// PACED (JENGA_FLAG_PACED_WALK): the selected blocks are not visited in list order.  A position G sweeps
+// over the key blocks once per lap, derived from the constant-frequency clock that every CU reads
+// (s_memrealtime), and a workgroup always takes the first block of its list that it has not visited yet
+// at or after G (wrapping around).  Softmax attention does not depend on the order of the keys, so the
+// result is the same up to rounding; what changes is when a tile is asked for: all workgroups of an XCD
+// now ask for neighbouring tiles at neighbouring times, and the 4 MB L2, which catches a seventh of the
+// tile reads of the in-order walk, catches more than half of them (measured on the 720p workload).
+// The price: the order, and with it the last bits of the output, can differ from run to run.
 // ---------------------------------------------------------------------------------------------
-template <int D>
+template <int D, bool PACED>
 __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     const uint16_t* __restrict__ q, const u32x4* __restrict__ kp, const u32x4* __restrict__ vp,
     const int32_t* __restrict__ sel_count, const int32_t* __restrict__ sel_index,
     const int32_t* __restrict__ blk_valid, uint16_t* __restrict__ out, float* __restrict__ lse, int n_bh, int M,
-    int M_v, int n_pad, int chunk, int pad_v, int pad_c, float scale_log2e, float bias_log2e) {
+    int M_v, int n_pad, int chunk, int pad_v, int pad_c, float scale_log2e, float bias_log2e,
+    const uint32_t* __restrict__ pace_params) {
   constexpr int BLK = 128, KS = D / 16, DT = D / 32, PS = BLK / 16, MH = 2, PH = 4;
   constexpr int TILE_CHUNKS = BLK * D / 8, HALF_CHUNKS = TILE_CHUNKS / 2, CPT = HALF_CHUNKS / 256;
   __shared__ u32x4 Ks[HALF_CHUNKS];   // fragments (m2, ks) of the current 64 keys
   __shared__ u32x4 Vs[HALF_CHUNKS];   // fragments (dt, p2) of the current 64 keys
+  __shared__ uint32_t rem_bits[PACED ? 64 : 1];   // PACED: bitmap of the blocks still to visit, 32 per word
+  __shared__ int pace_slot[2];                    // PACED: G for the next pick, published by thread 0
 
   int bh, i;
   if (!map_work(blockIdx.x, n_bh, M, M_v, chunk, &bh, &i)) return;
@@ -381,8 +401,44 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 
   int cnt = sel_count[(size_t)bh * M + i];
   cnt = min(max(cnt, 0), M);
-  const int steps = 2 * cnt;
   const int32_t* idx = sel_index + ((size_t)bh * M + i) * M;
+  uint32_t rem = 0, pace_k = 0;
+  if constexpr (PACED) {
+    // the list as a bitmap (a block listed twice is visited once); lane w of every wavefront holds word w
+    pace_k = pace_params[0];
+    if (tid < 64) rem_bits[tid] = 0;
+    __syncthreads();
+    for (int t = tid; t < cnt; t += 256) {
+      const int jj = min(max(idx[t], 0), M - 1);
+      atomicOr(&rem_bits[jj >> 5], 1u << (jj & 31));
+    }
+    __syncthreads();
+    rem = rem_bits[lane];
+    int pc = __popc(rem);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) pc += __shfl_xor(pc, o, 64);
+    cnt = __builtin_amdgcn_readfirstlane(pc);
+  }
+  // G: the low 32 bits of the clock times 2^32 / lap wrap once per lap; the high half of that times M is the block
+  auto pace_now = [&]() { return (int)__umulhi((uint32_t)__builtin_amdgcn_s_memrealtime() * pace_k, (uint32_t)M); };
+  // The first remaining block at or after G, else the first one after the wrap.  Every wavefront runs this on its
+  // own copy of the bitmap with the same G, so the four agree without exchanging the result.  Needs rem != 0.
+  auto pick = [&](int G) {
+    const int w0 = G >> 5, b0 = G & 31;
+    const uint32_t low = (1u << b0) - 1u;
+    uint32_t mw = lane == w0 ? rem & ~low : rem;
+    uint64_t bal = __ballot(lane >= w0 && mw != 0);
+    if (bal == 0) {
+      mw = lane == w0 ? rem & low : rem;
+      bal = __ballot(lane <= w0 && mw != 0);
+    }
+    const int src = __builtin_ctzll(bal);
+    const int bit = __builtin_ctz(mw | 0x80000000u);
+    const int jp = __builtin_amdgcn_readlane(lane * 32 + bit, src);
+    if (lane == src) rem &= ~(1u << bit);
+    return jp;
+  };
+  const int steps = 2 * cnt;
   const u32x4* kbase = kp + (size_t)bh * M * TILE_CHUNKS;
   const u32x4* vbase = vp + (size_t)bh * M * TILE_CHUNKS;
 
@@ -411,7 +467,14 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 
   // The block index of the next step is fetched a step ahead, and the valid-token count of a
   // block follows from its index, so no step waits on a scalar load it has just issued.
-  int j_next = cnt > 0 ? min(max(idx[0], 0), M - 1) : 0;
+  int j_next = 0;
+  if constexpr (PACED) {
+    if (tid == 0) pace_slot[0] = pace_now();
+    __syncthreads();
+    if (cnt > 0) j_next = pick(pace_slot[0]);
+  } else {
+    if (cnt > 0) j_next = min(max(idx[0], 0), M - 1);
+  }
   if (cnt > 0) k_half_to_lds(j_next, 0);
 
   for (int st = 0; st < steps; ++st) {
@@ -451,7 +514,17 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
       });
     }
 
-    j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
+    if constexpr (PACED) {
+      // G is sampled during the first half step of a block (the clock read has time to return under the
+      // softmax) and turned into the next block by every wavefront during the second half step
+      if (h == 0) {
+        if (tid == 0) pace_slot[((st >> 1) + 1) & 1] = pace_now();
+      } else if (st + 1 < steps) {
+        j_next = pick(pace_slot[((st >> 1) + 1) & 1]);                 // used after the next barrier
+      }
+    } else {
+      j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
+    }
 
     // ---- online softmax on S^T (lane = query row, registers = keys) ----
     const int nv = BLK - (j == M_v - 1 ? pad_v : (j == M - 1 ? pad_c : 0));
@@ -540,6 +613,25 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     }
 }
 
+// Lap of the paced walk, common to all workgroups of a launch: a fixed fraction of the time a workgroup needs for
+// a list of mean length, so that a workgroup goes round a little less than twice.  Writes 2^32 / lap (in ticks of
+// the 100 MHz clock) to params[0].  One workgroup.
+__global__ __launch_bounds__(256) void walk_pace_kernel(const int32_t* __restrict__ sel_count, int n_rows, int M,
+                                                        float ticks_per_block, uint32_t* __restrict__ params) {
+  __shared__ float part[4];
+  float s = 0.f;
+  for (int t = threadIdx.x; t < n_rows; t += 256) s += (float)min(max(sel_count[t], 0), M);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const float mean = (part[0] + part[1] + part[2] + part[3]) / (float)max(n_rows, 1);
+    const float lap = fminf(fmaxf(0.6f * mean * ticks_per_block, 1024.f), 1e9f);
+    params[0] = (uint32_t)(4294967296.0 / (double)lap);
+  }
+}
+
 template <int BLK, int D>
 int run_pack(const jenga_plan* p, const void* k, const void* v, void* ws, hipStream_t st) {
   const jenga_config& c = p->cfg;
@@ -554,7 +646,7 @@ int run_pack(const jenga_plan* p, const void* k, const void* v, void* ws, hipStr
 }
 
 template <int BLK, int D>
-int run_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
+int run_attention(const jenga_plan* p, const void* q, void* ws, const int32_t* sel_count,
                   const int32_t* sel_index, void* out, float* lse, hipStream_t st) {
   const jenga_config& c = p->cfg;
   const jenga_plan_info_t& f = p->info;
@@ -566,14 +658,25 @@ int run_attention(const jenga_plan* p, const void* q, const void* ws, const int3
   const int n_wg = bh * f.M_c + bh * 8 * chunk;           // text blocks first, then the vision runs
   const float log2e = 1.4426950408889634f;
   const float scale = log2e / sqrtf((float)D);
-  if constexpr (BLK == 128)
-    attn_h_kernel<D><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
+  if constexpr (BLK == 128) {
+    if (c.flags & JENGA_FLAG_PACED_WALK) {
+      // a workgroup spends about 6.3 us (D = 128; 3.6 us at D = 64) on a block of 128 keys when three share a CU
+      uint32_t* params = (uint32_t*)((char*)ws + 2 * half);
+      walk_pace_kernel<<<1, 256, 0, st>>>(sel_count, bh * f.M, f.M, D == 128 ? 630.f : 360.f, params);
+      attn_h_kernel<D, true><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
+                                                         p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v, f.N_pad,
+                                                         chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e, params);
+    } else {
+      attn_h_kernel<D, false><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
                                                           p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v,
-                                                          f.N_pad, chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e);
+                                                          f.N_pad, chunk, f.pad_v, f.pad_c, scale,
+                                                          c.text_bias * log2e, nullptr);
+    }
+  }
   else
     attn_kernel<BLK, D><<<dim3(n_wg), AttnTraits<BLK, D>::NTHR, 0, st>>>(
         (const uint16_t*)q, kp, vp, sel_count, sel_index, p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v,
-        f.N_pad, chunk, scale, c.text_bias * log2e);
+        f.N_pad, chunk, scale, c.text_bias * log2e);   // blocks of 32 or 64 tokens: in-order walk only
   return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_EHIP;
 }
 
@@ -593,7 +696,7 @@ int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, voi
   return JENGA_EUNSUPPORTED;
 }
 
-int launch_attention(const jenga_plan* p, const void* q, const void* ws, const int32_t* sel_count,
+int launch_attention(const jenga_plan* p, const void* q, void* ws, const int32_t* sel_count,
                      const int32_t* sel_index, void* out, float* lse, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const int blk = p->cfg.block, d = p->cfg.head_dim;

@@ -121,7 +121,7 @@ int jenga_pack_kv(const jenga_plan* p, const void* k, const void* v, void* works
   return jenga::launch_pack(p, k, v, workspace, stream);
 }
 
-int jenga_block_sparse_attn_packed(const jenga_plan* p, const void* q, const void* packed_kv_workspace,
+int jenga_block_sparse_attn_packed(const jenga_plan* p, const void* q, void* packed_kv_workspace,
                                    size_t workspace_bytes, const int32_t* sel_count, const int32_t* sel_index,
                                    void* out_curve, float* lse_or_null, void* stream) {
   if (!p || !q || !packed_kv_workspace || !sel_count || !sel_index || !out_curve) return JENGA_EINVAL;

@@ -15,7 +15,7 @@ bool config_ok(const jenga_config& c, int* why) {
   if (!(c.topk_ratio > 0.0 && c.topk_ratio <= 1.0)) return false;
   if (!(c.cum_prob >= 0.0 && c.cum_prob < 1.0)) return false;
   if (!std::isfinite(c.text_bias)) return false;   // NaN and +-inf: exp2(-inf + inf) would poison a row
-  if (c.flags & ~7u) return false;
+  if (c.flags & ~15u) return false;
   *why = JENGA_EUNSUPPORTED;
   if (c.head_dim != 64 && c.head_dim != 128) return false;
   if (c.block != 32 && c.block != 64 && c.block != 128) return false;

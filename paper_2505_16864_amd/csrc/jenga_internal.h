@@ -40,7 +40,7 @@ int launch_select(const jenga_plan* p, const void* q, const void* k, int32_t* se
 // Looks up the address of the static selection scratch on `device` (the current device) once.
 int select_scratch_init(int device);
 int launch_pack(const jenga_plan* p, const void* k, const void* v, void* ws, void* stream);
-int launch_attention(const jenga_plan* p, const void* q, const void* packed_ws, const int32_t* sel_count,
+int launch_attention(const jenga_plan* p, const void* q, void* packed_ws, const int32_t* sel_count,
                      const int32_t* sel_index, void* out, float* lse, void* stream);
 
 }  // namespace jenga

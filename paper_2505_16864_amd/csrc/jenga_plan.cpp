@@ -194,7 +194,7 @@ int build_host_tables(jenga_plan* plan) {
   f.select_workspace_bytes = align256(bh * f.M_v * c.head_dim * 8) + align256(bh * f.M * c.head_dim * 8) +
                              align256(bh * (uint64_t)f.M_v * f.M * 8);
   // attention: K and V re-tiled, bf16, one tile per (batch, head, block)
-  f.attn_workspace_bytes = 2 * align256(bh * (uint64_t)f.N_pad * c.head_dim * 2);
+  f.attn_workspace_bytes = 2 * align256(bh * (uint64_t)f.N_pad * c.head_dim * 2) + 256;   // packed K, packed V, launch parameters
   return JENGA_OK;
 }
 

@@ -8,10 +8,12 @@ class CarveLayer:
     """Allocates the curve-side tensors, index lists and workspaces of one configuration once and
     runs the four calls on torch's current stream."""
 
-    def __init__(self, w, device="cuda:0", text_bias=None, flags=7, want_mask=False, want_lse=False):
+    def __init__(self, w, device="cuda:0", text_bias=None, flags=None, want_mask=False, want_lse=False):
         self.w = dict(w)
         if text_bias is None:
             text_bias = w.get("text_bias", 0.0)
+        if flags is None:
+            flags = w.get("flags", 7)
         self.device = torch.device(device)
         self.cfg = B.make_config(w["T"], w["H"], w["W"], w["n_text"], w["batch"], w["heads"], w["head_dim"],
                                  w["block"], w["topk"], w["p"], text_bias, flags)

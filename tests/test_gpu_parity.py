@@ -190,6 +190,62 @@ def test_log_sum_exp(name, beta):
     assert np.isneginf(layer.lse.cpu().numpy()).all()
 
 
+# The time-paced walk (flag bit 3): same set of blocks, visited in an order that depends on a clock.  Same masks,
+# outputs within the same tolerance, log-sum-exp within 1e-3; two runs agree within rounding, not bit for bit.
+@pytest.mark.parametrize("name,beta", [("small", 0.0), ("ragged_m128_d128", 0.0), ("ragged_m128_d128", 0.5),
+                                       ("m128_d64", -0.5 * math.log(0.5625)), ("one_token_each", 0.0)])
+def test_paced_walk(name, beta):
+    w, (q, k, v), layer, out, lay = _run(name, seed=23, flags=15, text_bias=beta, want_lse=True)
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    mask = jo.build_mask(qc, kc, lay, w["p"])
+    assert np.array_equal(layer.mask.cpu().numpy().astype(bool), mask)
+    want_o, want_lse = jo.block_sparse_attention(qc, kc, vc, mask, lay, beta=beta, return_lse=True)
+    check_output(to_f64(layer.o_c), want_o, name + " paced walk")
+    got_lse = layer.lse.cpu().numpy().astype(np.float64)
+    assert np.isneginf(got_lse[:, :, ~lay.valid]).all()
+    assert np.abs(got_lse[:, :, lay.valid] - want_lse[:, :, lay.valid]).max() <= 1e-3
+    assert not ji.bits(layer.o_c)[:, :, ~lay.valid].any()
+    first = to_f64(layer.o_c).copy()
+    for _ in range(3):                      # the order may change from run to run, the result only within rounding
+        layer.o_c.view(torch.int16).fill_(0x7FC1)
+        layer.attend()
+        torch.cuda.synchronize()
+        again = to_f64(layer.o_c)
+        assert np.abs(again - first).max() <= 2 ** -7 * max(1.0, np.abs(first).max())
+        check_output(again, want_o, name + " paced walk, repeated")
+
+
+def test_paced_walk_with_given_lists_and_duplicates():
+    # lists in random order with every block listed twice: the paced walk visits each block once
+    w = dict(CASES["ragged_m128_d128"])
+    q, k, v = ji.make_qkv(w, 24)
+    layer = CarveLayer(w, "cuda:0", flags=15)
+    lay = oracle_layout(w)
+    rng = np.random.default_rng(3)
+    mask = rng.random((w["batch"], w["heads"], lay.M, lay.M)) < 0.45
+    mask[:, :, np.arange(lay.M), np.arange(lay.M)] = True
+    cnt, idx = jo.mask_to_lists(mask)
+    idx2 = np.full((w["batch"], w["heads"], lay.M, lay.M), -1, dtype=np.int32)
+    cnt2 = np.zeros_like(cnt)
+    for h in range(idx.shape[1]):
+        for i in range(lay.M):
+            n = cnt[0, h, i]
+            twice = rng.permutation(np.concatenate([idx[0, h, i, :n], idx[0, h, i, :n]]))[: lay.M]
+            keep = set(twice.tolist())
+            mask[0, h, i] = False
+            mask[0, h, i, list(keep)] = True
+            idx2[0, h, i, : len(twice)] = twice
+            cnt2[0, h, i] = len(twice)
+    layer.permute_in(q.cuda(), k.cuda(), v.cuda())
+    layer.sel_count.copy_(torch.from_numpy(cnt2))
+    layer.sel_index.copy_(torch.from_numpy(idx2))
+    layer.o_c.view(torch.int16).fill_(0x7FC1)
+    layer.attend()
+    torch.cuda.synchronize()
+    qc, kc, vc = [jo.permute(to_f64(x), lay) for x in (q, k, v)]
+    check_output(to_f64(layer.o_c), jo.block_sparse_attention(qc, kc, vc, mask, lay), "paced, duplicates")
+
+
 def test_attention_with_given_lists_and_constant_values():
     # feed the oracle's lists of a random mask (not produced by selection) and a constant V
     w = dict(CASES["ragged_m128_d128"])

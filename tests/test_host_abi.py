@@ -79,13 +79,13 @@ def test_k_top_and_workspace_sizes():
     assert info.K_top == 78 and info.M == 262
     info = J.jenga_plan_tables(J.make_config(33, 45, 80, 256, 1, 24, 128, 128, 0.3, 0.3))
     assert (info.M_v, info.pad_v, info.M, info.N_pad, info.K_top) == (929, 112, 931, 119168, 278)
-    assert info.attn_workspace_bytes == 2 * 24 * 119168 * 128 * 2
+    assert info.attn_workspace_bytes == 2 * 24 * 119168 * 128 * 2 + 256
     assert info.select_workspace_bytes >= 24 * (929 + 931) * 128 * 8 + 24 * 929 * 931 * 8
 
 
 @pytest.mark.parametrize("bad,status", [
     (dict(T=0), -1), (dict(n_text=-1), -1), (dict(batch=0), -1), (dict(heads=0), -1),
-    (dict(topk=0.0), -1), (dict(topk=1.5), -1), (dict(p=1.0), -1), (dict(p=-0.1), -1), (dict(flags=8), -1),
+    (dict(topk=0.0), -1), (dict(topk=1.5), -1), (dict(p=1.0), -1), (dict(p=-0.1), -1), (dict(flags=16), -1),
     (dict(text_bias=float("nan")), -1), (dict(text_bias=float("inf")), -1), (dict(text_bias=float("-inf")), -1),
     # Alg. 2's text-only branch (no vision tokens) is plain dense attention and is not taken by this library
     (dict(T=0, H=0, W=0), -1), (dict(W=0), -1),

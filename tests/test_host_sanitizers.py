@@ -46,7 +46,7 @@ VALID = [  # T H W n_text batch heads d m k p beta flags
 INVALID = [  # (config, expected status)
     ((0, 8, 8, 32, 1, 2, 64, 32, 0.25, 0.3, 0.0, 7), -1), ((4, 8, 8, -1, 1, 2, 64, 32, 0.25, 0.3, 0.0, 7), -1),
     ((4, 8, 8, 32, 1, 2, 64, 32, 0.0, 0.3, 0.0, 7), -1), ((4, 8, 8, 32, 1, 2, 64, 32, 0.25, 1.0, 0.0, 7), -1),
-    ((4, 8, 8, 32, 1, 2, 64, 32, 0.25, 0.3, 0.0, 8), -1), ((4, 8, 8, 32, 1, 2, 96, 32, 0.25, 0.3, 0.0, 7), -2),
+    ((4, 8, 8, 32, 1, 2, 64, 32, 0.25, 0.3, 0.0, 16), -1), ((4, 8, 8, 32, 1, 2, 96, 32, 0.25, 0.3, 0.0, 7), -2),
     ((4, 8, 8, 32, 1, 2, 64, 16, 0.25, 0.3, 0.0, 7), -2), ((400, 400, 400, 32, 1, 2, 64, 32, 0.25, 0.3, 0.0, 7), -2),
     ((8, 64, 128, 512, 1, 2, 64, 32, 0.05, 0.3, 0.0, 7), -2),   # M = 2064 > 2048
     ((2147483647, 2147483647, 2, 0, 1, 1, 64, 32, 0.5, 0.0, 0.0, 7), -2),   # products that overflow 32 bits
