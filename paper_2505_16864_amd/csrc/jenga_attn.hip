@@ -614,8 +614,12 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 }
 
 // Lap of the paced walk, common to all workgroups of a launch: a fixed fraction of the time a workgroup needs for
-// a list of mean length, so that a workgroup goes round a little less than twice.  Writes 2^32 / lap (in ticks of
+// a list of mean length (a tuning constant: between 0.45 and 0.9 the measured time is flat, at 1.0 and above the
+// workgroups run ahead of the sweep and the gain goes).  Writes 2^32 / lap (in ticks of
 // the 100 MHz clock) to params[0].  One workgroup.
+#ifndef JENGA_PACE_FACTOR
+#define JENGA_PACE_FACTOR 0.6f
+#endif
 __global__ __launch_bounds__(256) void walk_pace_kernel(const int32_t* __restrict__ sel_count, int n_rows, int M,
                                                         float ticks_per_block, uint32_t* __restrict__ params) {
   __shared__ float part[4];
@@ -627,7 +631,7 @@ __global__ __launch_bounds__(256) void walk_pace_kernel(const int32_t* __restric
   __syncthreads();
   if (threadIdx.x == 0) {
     const float mean = (part[0] + part[1] + part[2] + part[3]) / (float)max(n_rows, 1);
-    const float lap = fminf(fmaxf(0.6f * mean * ticks_per_block, 1024.f), 1e9f);
+    const float lap = fminf(fmaxf(JENGA_PACE_FACTOR * mean * ticks_per_block, 1024.f), 1e9f);
     params[0] = (uint32_t)(4294967296.0 / (double)lap);
   }
 }
