@@ -277,7 +277,7 @@ def main():
     traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "attn_kernel_%s_traffic.json" % args.workload)
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        traffic = json.load(open(tpath)).get(args.walk, {}).get("hbm_bytes_per_launch")
         traffic_source = "profiles/" + os.path.basename(tpath) + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 
     out = {

@@ -620,17 +620,25 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 #ifndef JENGA_PACE_FACTOR
 #define JENGA_PACE_FACTOR 0.6f
 #endif
-__global__ __launch_bounds__(256) void walk_pace_kernel(const int32_t* __restrict__ sel_count, int n_rows, int M,
-                                                        float ticks_per_block, uint32_t* __restrict__ params) {
-  __shared__ float part[4];
+__global__ __launch_bounds__(1024) void walk_pace_kernel(const int32_t* __restrict__ sel_count, int n_rows, int M,
+                                                         float ticks_per_block, uint32_t* __restrict__ params) {
+  __shared__ float part[16];
   float s = 0.f;
-  for (int t = threadIdx.x; t < n_rows; t += 256) s += (float)min(max(sel_count[t], 0), M);
+  for (int t0 = threadIdx.x; t0 < n_rows; t0 += 4096) {   // four loads in flight per thread
+    int c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) c[u] = t0 + u * 1024 < n_rows ? sel_count[t0 + u * 1024] : 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) s += (float)min(max(c[u], 0), M);
+  }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
   if (threadIdx.x == 0) {
-    const float mean = (part[0] + part[1] + part[2] + part[3]) / (float)max(n_rows, 1);
+    float total = 0.f;
+    for (int w = 0; w < 16; ++w) total += part[w];
+    const float mean = total / (float)max(n_rows, 1);
     const float lap = fminf(fmaxf(JENGA_PACE_FACTOR * mean * ticks_per_block, 1024.f), 1e9f);
     params[0] = (uint32_t)(4294967296.0 / (double)lap);
   }
@@ -666,7 +674,7 @@ int run_attention(const jenga_plan* p, const void* q, void* ws, const int32_t* s
     if (c.flags & JENGA_FLAG_PACED_WALK) {
       // a workgroup spends about 6.3 us (D = 128; 3.6 us at D = 64) on a block of 128 keys when three share a CU
       uint32_t* params = (uint32_t*)((char*)ws + 2 * half);
-      walk_pace_kernel<<<1, 256, 0, st>>>(sel_count, bh * f.M, f.M, D == 128 ? 630.f : 360.f, params);
+      walk_pace_kernel<<<1, 1024, 0, st>>>(sel_count, bh * f.M, f.M, D == 128 ? 630.f : 360.f, params);
       attn_h_kernel<D, true><<<dim3(n_wg), 256, 0, st>>>((const uint16_t*)q, kp, vp, sel_count, sel_index,
                                                          p->d_blk_valid, (uint16_t*)out, lse, bh, f.M, f.M_v, f.N_pad,
                                                          chunk, f.pad_v, f.pad_c, scale, c.text_bias * log2e, params);
