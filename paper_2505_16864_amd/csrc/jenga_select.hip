@@ -196,13 +196,18 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
   }
 
   // value of the K_top-th largest: largest pattern with count(key >= pattern) >= K_top
+  // The descent stops as soon as exactly K_top values lie at or above the pattern built so far: that set is the
+  // answer whatever the remaining bits are (typically after 20-25 of the 63 bits).
   uint64_t tau_k = 0;
   for (int bit = 62; bit >= 0; --bit) {
     const uint64_t cand = tau_k | (1ull << bit);
     int cnt = 0;
 #pragma unroll
     for (int t = 0; t < NT; ++t) cnt += __popcll(__ballot(key[t] >= cand));
-    if (cnt >= K_top) tau_k = cand;
+    if (cnt >= K_top) {
+      tau_k = cand;
+      if (cnt == K_top) break;
+    }
   }
   int cnt_gt = 0;
   double sum_gt = 0.0;
@@ -219,6 +224,8 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
   int n_keep = K_top;
   if (!(topk_mass > p)) {
     // cumulative-probability rule: largest pattern whose upper set still sums to more than p
+    // The answer is one of the row's values.  After bit b it lies in [tau_p, tau_p + 2^b); once that interval
+    // holds a single value, that value is the answer and the remaining bits are its bits.
     uint64_t tau_p = 0;
     for (int bit = 62; bit >= 0; --bit) {
       const uint64_t cand = tau_p | (1ull << bit);
@@ -227,6 +234,23 @@ __global__ __launch_bounds__(256) void select_kernel(const double* __restrict__ 
       for (int t = 0; t < NT; ++t) f += key[t] >= cand ? r[t] : 0.0;
       f = wave_sum(f);
       if (f > p) tau_p = cand;
+      const uint64_t hi = tau_p + (1ull << bit);     // exclusive end of the interval that still holds the answer
+      int inside = 0;
+      uint64_t mine = 0;
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const bool in = key[t] >= tau_p && key[t] < hi;
+        inside += __popcll(__ballot(in));
+        if (in) mine = key[t];
+      }
+      if (inside == 1) {
+        const uint64_t who = __ballot(mine != 0);
+        const int src = __builtin_ctzll(who);
+        const uint32_t lo32 = __builtin_amdgcn_readlane((uint32_t)mine, src);
+        const uint32_t hi32 = __builtin_amdgcn_readlane((uint32_t)(mine >> 32), src);
+        tau_p = ((uint64_t)hi32 << 32) | lo32;
+        break;
+      }
     }
     int g_cnt = 0, e_cnt = 0;
     double g_sum = 0.0;
