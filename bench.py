@@ -281,7 +281,7 @@ def main():
         traffic_source = "profiles/" + os.path.basename(tpath) + " (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 
     out = {
-        "metric": "ms per block-sparse attention layer (select + attention)",
+        "metric": "ms per block-sparse attention layer (select + pack + attention)",
         "value": layer_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

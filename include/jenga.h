@@ -58,7 +58,9 @@ enum {
 
 /* Problem statement of one layer (Sec. 3.1; Alg. 2 and Alg. 3 inputs). */
 typedef struct {
-  int32_t T, H, W;     /* latent grid; N_v = T*H*W vision tokens                              */
+  int32_t T, H, W;     /* latent grid, each >= 1; N_v = T*H*W vision tokens.  A layer without vision
+                          tokens (the text-only branch of Alg. 2) is plain dense attention and is not
+                          taken: JENGA_EINVAL                                                  */
   int32_t n_text;      /* N_c >= 0 condition tokens, stored behind the vision tokens           */
   int32_t batch;       /* >= 1                                                                 */
   int32_t heads;       /* >= 1                                                                 */
