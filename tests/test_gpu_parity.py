@@ -215,6 +215,15 @@ def test_paced_walk(name, beta):
         check_output(again, want_o, name + " paced walk, repeated")
 
 
+def test_paced_walk_flag_is_ignored_for_other_block_sizes():
+    # blocks of 32 and 64 tokens have the in-order walk only: with the flag the output is the same, bit for bit
+    for name in ("ragged_m32_d64", "ragged_m64_d128"):
+        w, (q, k, v), layer, out, lay = _run(name, seed=25, flags=15)
+        paced = ji.bits(out).copy()
+        w, (q, k, v), layer, out, lay = _run(name, seed=25, flags=7)
+        assert np.array_equal(ji.bits(out), paced)
+
+
 def test_paced_walk_with_given_lists_and_duplicates():
     # lists in random order with every block listed twice: the paced walk visits each block once
     w = dict(CASES["ragged_m128_d128"])
