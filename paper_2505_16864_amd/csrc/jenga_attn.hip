@@ -4,8 +4,9 @@
 // One workgroup owns one query block of BLK rows of one (batch, head): BLK/32 wavefronts, each with
 // 32 query rows.  It walks the ascending list of selected key blocks.  Per key block:
 //     S^T = K Q^T         v_mfma_f32_32x32x16_bf16, K fragments from LDS, Q fragments in registers
-//     online softmax      float32, base-2 exponent, statistics per query row; the reference maximum
-//                         moves lazily (rescale_if_grown), row sums are float32 sums of P
+//     online softmax      float32, base-2 exponent, statistics per query row; the reference the
+//                         exponent is taken against moves lazily (128-token blocks: only when a row
+//                         sum leaves its range), row sums are float32 sums of P
 //     O^T += V^T P^T      v_mfma_f32_32x32x16_bf16, V^T fragments from LDS, P^T straight from the
 //                         S^T accumulators
 // Working on the transposed products keeps one query row in one lane (column) of every
@@ -93,17 +94,22 @@ __global__ __launch_bounds__(256) void pack_kernel(const uint16_t* __restrict__ 
 // Written as asm so that the compiler does not track these copies: it would otherwise order every
 // later LDS read of the same array behind them with a full vmcnt(0) wait.  Completion is tracked by
 // vmcnt and waited for explicitly (wait_vmem) before the barrier that publishes a tile.
-__device__ inline void dma_1kb_to_lds(const void* uniform_base, uint32_t lane_byte_off, const void* lds_dst) {
+// dma_1kb_to_lds_at takes the LDS byte address as a number the caller keeps in an SGPR;
+// dma_1kb_to_lds derives it from a pointer (a few more instructions per copy).
+__device__ inline void dma_1kb_to_lds_at(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_addr) {
   const uint64_t b = (uint64_t)uniform_base;
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
   const uint64_t base = ((uint64_t)hi << 32) | lo;
-  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_dst);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                :
                : "s"(lds_addr), "v"(lane_byte_off), "s"(base)
                : "memory", "m0");
+}
+__device__ inline void dma_1kb_to_lds(const void* uniform_base, uint32_t lane_byte_off, const void* lds_dst) {
+  dma_1kb_to_lds_at(uniform_base, lane_byte_off,
+                    __builtin_amdgcn_readfirstlane(
+                        (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_dst));
 }
 
 // Straight copy of one packed tile (global, fragment order) into LDS without passing through
@@ -352,6 +358,18 @@ __device__ inline float max_with_other_half(float x) {
 #endif
 }
 
+// attn_h_kernel takes the lazy reference one step further and drops the row maximum from the common
+// path.  The vector ALU port is shared with the issue of the MFMAs; measured, the exponentials, their
+// FMAs, the row sums and the bf16 packing of a step just fit beside its 32 MFMAs, and the 16 v_max3
+// with what follows them do not.  So a step forms its probabilities against the reference as it
+// stands and only looks at the sum: while a lane's 32 probabilities add up to at most P_SUM_MAX they
+// are all representable, and so are the float32 sums and products built from them (bf16 and float32
+// share the exponent range; 2^30 times the row length times |V| stays far below 2^127).  A sum above
+// the bound, infinite or undefined sends the step down the exact path: logits again (the K half is
+// still in LDS), row maximum, rescale, probabilities <= 1.  The first step of a row starts there.
+// The reference never exceeds the largest logit seen, so the largest term is never lost to underflow.
+constexpr float P_SUM_MAX = 1073741824.0f;   // 2^30
+
 // ---------------------------------------------------------------------------------------------
 // attn_h_kernel: blocks of 128 tokens, walked in half blocks of 64 keys.
 //
@@ -444,19 +462,26 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
 
   // K half h of block j is one contiguous run of the packed tile; V half h is PH fragments out of
   // every PS of each channel tile: wave w copies fragments f = c*4 + w, f = dt*PH + p2
+  const uint32_t ks_wave = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)Ks + (uint32_t)wave * 1024u);
+  const uint32_t vs_wave = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)Vs + (uint32_t)wave * 1024u);
   auto k_half_to_lds = [&](int j, int h) {
-    tile_to_lds<256, CPT>(kbase + (size_t)j * TILE_CHUNKS + h * HALF_CHUNKS, Ks, tid, wave);
+    const char* kt = (const char*)(kbase + (size_t)j * TILE_CHUNKS + h * HALF_CHUNKS);
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) dma_1kb_to_lds_at(kt + (size_t)c * 4096, (uint32_t)tid * 16u, ks_wave + c * 4096u);
   };
   auto v_half_to_lds = [&](int j, int h) {
     const u32x4* vt = vbase + (size_t)j * TILE_CHUNKS + (PH * h) * 64;
 #pragma unroll
     for (int c = 0; c < CPT; ++c) {
       const int f = c * 4 + wave, dt = f / PH, p2 = f % PH;
-      dma_1kb_to_lds(vt + (size_t)(dt * PS + p2) * 64, (uint32_t)lane * 16u, Vs + f * 64);
+      dma_1kb_to_lds_at(vt + (size_t)(dt * PS + p2) * 64, (uint32_t)lane * 16u, vs_wave + c * 4096u);
     }
   };
 
   float m_run = -INFINITY, l_run = 0.f;
+  bool unset = true;   // no row has a reference yet (uniform: every row sees the same keys)
   f32x16 O[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -484,86 +509,122 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
     __syncthreads();   // K half of this step is in LDS; every wave is past the previous PV
     v_half_to_lds(j, h);
 
-    // S^T = K Q^T.  Fragments come in groups of four, (m2, ks) = (e & 1, 2g + e / 2); group g + 1 is
-    // in flight while the MFMAs of group g run, and the two accumulators alternate.
+    // S^T = K Q^T for the 64 keys of this step, with the pad keys of a ragged block set to -inf.  Fragments come in
+    // groups of four, (m2, ks) = (e & 1, 2g + e / 2); group g + 1 is in flight while the MFMAs of group g run, and
+    // the two accumulators alternate.
     f32x16 S[MH];
-#pragma unroll
-    for (int m2 = 0; m2 < MH; ++m2)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) S[m2][r] = 0.f;
-    {
-      constexpr int NG = KS / 2;
-      u32x4 A[2][4];
-      static_for<4>([&](auto E) {
-        constexpr int e = decltype(E)::value;
-        lds_frag<((e & 1) * KS + e / 2) * 1024>(A[0][e], ks_lane);
-      });
-      static_for<NG>([&](auto G) {
-        constexpr int g = decltype(G)::value;
-        lds_wait(A[g & 1]);
-        if constexpr (g + 1 < NG)
-          static_for<4>([&](auto E) {
-            constexpr int e = decltype(E)::value;
-            lds_frag<((e & 1) * KS + 2 * (g + 1) + e / 2) * 1024>(A[(g + 1) & 1][e], ks_lane);
-          });
-        static_for<4>([&](auto E) {
-          constexpr int e = decltype(E)::value, m2 = e & 1, ks = 2 * g + e / 2;
-          S[m2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[g & 1][e]), qf[ks], S[m2],
-                                                          0, 0, 0);
-        });
-      });
-    }
-
-    if constexpr (PACED) {
-      // G is sampled during the first half step of a block (the clock read has time to return under the
-      // softmax) and turned into the next block by every wavefront during the second half step
-      if (h == 0) {
-        if (tid == 0) pace_slot[((st >> 1) + 1) & 1] = pace_now();
-      } else if (st + 1 < steps) {
-        j_next = pick(pace_slot[((st >> 1) + 1) & 1]);                 // used after the next barrier
-      }
-    } else {
-      j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
-    }
-
-    // ---- online softmax on S^T (lane = query row, registers = keys) ----
     const int nv = BLK - (j == M_v - 1 ? pad_v : (j == M - 1 ? pad_c : 0));
-    if (nv < BLK) {   // sequence-length mask: pad keys of a ragged block
-      asm volatile("");   // a real, rarely taken branch
+    auto logits = [&]() {
 #pragma unroll
       for (int m2 = 0; m2 < MH; ++m2)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int kv = 64 * h + 32 * m2 + 8 * (r / 4) + 4 * hl + (r % 4);
-          if (kv >= nv) S[m2][r] = -INFINITY;
-        }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int m2 = 0; m2 < MH; ++m2)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[m2][r]);
-    mx = max_with_other_half(mx);
-    const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
-    rescale_if_grown(fmaf(mx, scale_log2e, bias), m_run, l_run, O);
-    const float off = m_run == -INFINITY ? 0.f : bias - m_run;   // every key so far was padding: keep it finite
-    float rs0 = 0.f, rs1 = 0.f;
-    bf16x8 pb[PH];
-#pragma unroll
-    for (int p2 = 0; p2 < PH; ++p2) {
-      uint32_t w[4];
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2], scale_log2e, off));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2 + 1], scale_log2e, off));
-        w[e2] = pack_bf16x2(p0, p1);
-        rs0 += p0;
-        rs1 += p1;
+        for (int r = 0; r < 16; ++r) S[m2][r] = 0.f;
+      {
+        constexpr int NG = KS / 2;
+        u32x4 A[2][4];
+        static_for<4>([&](auto E) {
+          constexpr int e = decltype(E)::value;
+          lds_frag<((e & 1) * KS + e / 2) * 1024>(A[0][e], ks_lane);
+        });
+        static_for<NG>([&](auto G) {
+          constexpr int g = decltype(G)::value;
+          lds_wait(A[g & 1]);
+          if constexpr (g + 1 < NG)
+            static_for<4>([&](auto E) {
+              constexpr int e = decltype(E)::value;
+              lds_frag<((e & 1) * KS + 2 * (g + 1) + e / 2) * 1024>(A[(g + 1) & 1][e], ks_lane);
+            });
+          static_for<4>([&](auto E) {
+            constexpr int e = decltype(E)::value, m2 = e & 1, ks = 2 * g + e / 2;
+            S[m2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[g & 1][e]), qf[ks], S[m2],
+                                                            0, 0, 0);
+          });
+        });
       }
-      u32x4 pw = {w[0], w[1], w[2], w[3]};
-      pb[p2] = __builtin_bit_cast(bf16x8, pw);
+
+      if (nv < BLK) {   // sequence-length mask: pad keys of a ragged block
+        asm volatile("");   // a real, rarely taken branch
+#pragma unroll
+        for (int m2 = 0; m2 < MH; ++m2)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int kv = 64 * h + 32 * m2 + 8 * (r / 4) + 4 * hl + (r % 4);
+            if (kv >= nv) S[m2][r] = -INFINITY;
+          }
+      }
+    };
+
+    // ---- online softmax on S^T (lane = query row, registers = keys) ----
+    const float bias = (i < M_v && j >= M_v) ? bias_log2e : 0.f;
+    bf16x8 pb[PH];
+    // P = 2^(S * scale + off) as bf16 fragments for the second product; returns this lane's sum of them
+    auto probabilities = [&](float off) {
+      float rs0 = 0.f, rs1 = 0.f;
+#pragma unroll
+      for (int p2 = 0; p2 < PH; ++p2) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2], scale_log2e, off));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(S[p2 >> 1][8 * (p2 & 1) + 2 * e2 + 1], scale_log2e, off));
+          w[e2] = pack_bf16x2(p0, p1);
+          rs0 += p0;
+          rs1 += p1;
+        }
+        u32x4 pw = {w[0], w[1], w[2], w[3]};
+        pb[p2] = __builtin_bit_cast(bf16x8, pw);
+      }
+      return rs0 + rs1;
+    };
+    // Common path: probabilities against the reference as it stands, no row maximum (see P_SUM_MAX).  Exact
+    // path: the logits again, the reference moved to the row maximum (the rescaling step of Alg. 4), and
+    // probabilities <= 1 in place of the first attempt.  Each branch forms and consumes its own S, so S never
+    // occupies registers beside a finished P.
+    // the block of the next step, looked up under the arithmetic of this one
+    auto advance = [&]() {
+      if constexpr (PACED) {
+        // G is sampled during the first half step of a block (the clock read has time to return under the
+        // softmax) and turned into the next block by every wavefront during the second half step
+        if (h == 0) {
+          if (tid == 0) pace_slot[((st >> 1) + 1) & 1] = pace_now();
+        } else if (st + 1 < steps) {
+          j_next = pick(pace_slot[((st >> 1) + 1) & 1]);                 // used after the next barrier
+        }
+      } else {
+        j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
+      }
+    };
+    float rs = 0.f;
+    bool in_range = false;
+    const bool first = unset;
+    if (!first) {
+      logits();
+      advance();
+      rs = probabilities(bias - m_run);
+      in_range = __ballot(!(rs <= P_SUM_MAX)) == 0;
     }
-    l_run += rs0 + rs1;
+    if (!in_range) {
+      asm volatile("");   // a real branch: the first step of a row, then almost never
+      logits();
+      if (first) advance();
+      float mx = -INFINITY;
+#pragma unroll
+      for (int m2 = 0; m2 < MH; ++m2)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[m2][r]);
+      mx = max_with_other_half(mx);
+      const float m_new = fmaxf(m_run, fmaf(mx, scale_log2e, bias));
+      const float alpha = m_new == m_run ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+      rs = probabilities(m_run == -INFINITY ? 0.f : bias - m_run);   // every key so far was padding: keep it finite
+      unset = __ballot(m_run == -INFINITY) != 0;
+    }
+    l_run += rs;
 
     wait_vmem();       // this wave's part of the V half has landed
     __syncthreads();   // V half is in LDS; every wave is done reading the K half

@@ -278,6 +278,53 @@ def test_attention_with_given_lists_and_constant_values():
     check_output(got, jo.block_sparse_attention(qc, kc, vc, mask, lay), "given lists")
 
 
+# Logits that climb by ~14 base-2 units per key block along the curve: with lists in ascending order the sums
+# of probabilities taken against an old reference leave any fixed range every few blocks, so the reference has
+# to move several times per row (Alg. 4's rescaling of l and O); descending lists never move it after the first
+# block.  Curve-side tensors are written directly; the oracle gets the same bits.
+@pytest.mark.parametrize("flags", [7, 15])
+@pytest.mark.parametrize("order", ["ascending", "descending", "shuffled"])
+@pytest.mark.parametrize("name", ["ragged_m128_d128", "ragged_m64_d128", "wide_M80"])
+def test_reference_moves_when_logits_grow_along_the_list(name, order, flags):
+    w = dict(CASES[name])
+    lay = oracle_layout(w)
+    B_, Hh, D = w["batch"], w["heads"], w["head_dim"]
+    layer = CarveLayer(w, "cuda:0", flags=flags, want_lse=True)
+    rng = np.random.default_rng(31)
+    ramp = np.linspace(0.0, 8.0 * math.sqrt(128.0 / D), lay.N_pad)[None, None, :, None]
+    qc = 1.0 + 0.25 * rng.standard_normal((B_, Hh, lay.N_pad, D))
+    kc = ramp * (1.0 + 0.25 * rng.standard_normal((B_, Hh, lay.N_pad, D)))
+    vc = rng.standard_normal((B_, Hh, lay.N_pad, D))
+    for x in (qc, kc, vc):
+        x[:, :, ~lay.valid] = 0.0
+    tq, tk, tv = [torch.from_numpy(x).to(torch.bfloat16) for x in (qc, kc, vc)]
+    layer.q_c.copy_(tq)
+    layer.k_c.copy_(tk)
+    layer.v_c.copy_(tv)
+    mask = rng.random((B_, Hh, lay.M, lay.M)) < 0.7
+    mask[:, :, np.arange(lay.M), np.arange(lay.M)] = True
+    cnt, idx = jo.mask_to_lists(mask)
+    for b in range(B_):
+        for h in range(Hh):
+            for i in range(lay.M):
+                n = cnt[b, h, i]
+                if order == "descending":
+                    idx[b, h, i, :n] = idx[b, h, i, :n][::-1]
+                elif order == "shuffled":
+                    idx[b, h, i, :n] = rng.permutation(idx[b, h, i, :n])
+    layer.sel_count.copy_(torch.from_numpy(cnt))
+    layer.sel_index.copy_(torch.from_numpy(idx))
+    layer.o_c.view(torch.int16).fill_(0x7FC1)
+    layer.attend()
+    torch.cuda.synchronize()
+    f64 = [to_f64(t) for t in (tq, tk, tv)]
+    want_o, want_lse = jo.block_sparse_attention(f64[0], f64[1], f64[2], mask, lay, return_lse=True)
+    assert np.median(want_lse[:, :, lay.valid]) > 40.0   # a row's logits really span tens of e-folds above 0
+    check_output(to_f64(layer.o_c), want_o, "%s %s flags %d" % (name, order, flags))
+    got = layer.lse.cpu().numpy().astype(np.float64)
+    assert np.abs(got[:, :, lay.valid] - want_lse[:, :, lay.valid]).max() <= 1e-3
+
+
 @pytest.mark.parametrize("name", ["ragged_m128_d128", "ragged_m64_d128"])
 def test_lists_in_any_order_give_the_same_attention(name):
     # Alg. 4 sums over a set of blocks: the order of the list must not matter beyond rounding
