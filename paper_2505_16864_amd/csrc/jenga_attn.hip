@@ -441,20 +441,21 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
   auto pace_now = [&]() { return (int)__umulhi((uint32_t)__builtin_amdgcn_s_memrealtime() * pace_k, (uint32_t)M); };
   // The first remaining block at or after G, else the first one after the wrap.  Every wavefront runs this on its
   // own copy of the bitmap with the same G, so the four agree without exchanging the result.  Needs rem != 0.
-  auto pick = [&](int G) {
-    const int w0 = G >> 5, b0 = G & 31;
-    const uint32_t low = (1u << b0) - 1u;
+  // G is wave-uniform, so most of this is scalar arithmetic.
+  auto pick = [&](int G_any_lane) {
+    const int G = __builtin_amdgcn_readfirstlane(G_any_lane);
+    const int w0 = G >> 5;
+    const uint32_t low = (1u << (G & 31)) - 1u;
     uint32_t mw = lane == w0 ? rem & ~low : rem;
-    uint64_t bal = __ballot(lane >= w0 && mw != 0);
-    if (bal == 0) {
-      mw = lane == w0 ? rem & low : rem;
-      bal = __ballot(lane <= w0 && mw != 0);
+    uint64_t bal = __builtin_amdgcn_ballot_w64(mw != 0) & (~0ull << w0);
+    if (bal == 0) {   // nothing left at or after G: every remaining block lies before it
+      mw = rem;
+      bal = __builtin_amdgcn_ballot_w64(rem != 0);
     }
     const int src = __builtin_ctzll(bal);
-    const int bit = __builtin_ctz(mw | 0x80000000u);
-    const int jp = __builtin_amdgcn_readlane(lane * 32 + bit, src);
-    if (lane == src) rem &= ~(1u << bit);
-    return jp;
+    const int bit = __builtin_ctz(__builtin_amdgcn_readlane(mw, src));
+    rem &= lane == src ? ~(1u << bit) : ~0u;
+    return src * 32 + bit;
   };
   const int steps = 2 * cnt;
   const u32x4* kbase = kp + (size_t)bh * M * TILE_CHUNKS;
