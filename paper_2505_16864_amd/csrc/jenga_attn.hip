@@ -657,13 +657,20 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
   }
 
   // ---- normalise and store: lane holds row qrow, channels 32*dt + 8*g + 4*hl + {0..3} ----
+  // The indices are derived again from the thread index (through an opaque copy, so that they are not the values
+  // computed before the loop): kept live across the loop they would cost registers there.
+  int tid_e = threadIdx.x;
+  asm volatile("" : "+v"(tid_e));
+  const int hl_e = (tid_e >> 5) & 1, ql_e = tid_e & 31;
+  const int row_e = 32 * wave + ql_e;
+  const size_t qrow_e = (size_t)bh * n_pad + (size_t)i * BLK + row_e;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const bool row_ok = (32 * wave + ql) < blk_valid[i] && l_tot > 0.f;
+  const bool row_ok = row_e < blk_valid[i] && l_tot > 0.f;
   const float inv = row_ok ? 1.0f / l_tot : 0.f;
   // natural-log sum of exp(logit) over the visited keys: the running maximum is in base-2 units
-  if (lse != nullptr && hl == 0)
-    lse[(size_t)bh * n_pad + qrow] = row_ok ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
-  uint16_t* orow = out + ((size_t)bh * n_pad + qrow) * D;
+  if (lse != nullptr && hl_e == 0)
+    lse[qrow_e] = row_ok ? (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
+  uint16_t* orow = out + qrow_e * D;
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -671,7 +678,7 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
       uint2 w;
       w.x = row_ok ? pack_bf16x2(O[dt][4 * g] * inv, O[dt][4 * g + 1] * inv) : 0u;
       w.y = row_ok ? pack_bf16x2(O[dt][4 * g + 2] * inv, O[dt][4 * g + 3] * inv) : 0u;
-      *(uint2*)(orow + 32 * dt + 8 * g + 4 * hl) = w;
+      *(uint2*)(orow + 32 * dt + 8 * g + 4 * hl_e) = w;
     }
 }
 

@@ -96,4 +96,4 @@ def test_attention_main_loops_do_not_spill(listing):
         if m and "attn_h_kernelILi128" in m.group(1) and not m.group(1).endswith(".kd"):
             assert int(re.search(r"\.vgpr_count:\s+(\d+)", b).group(1)) <= 168, m.group(1)
             # a few values that only the epilogue needs may sit in scratch over the loop; none is touched inside it
-            assert int(re.search(r"\.vgpr_spill_count:\s+(\d+)", b).group(1)) <= 8, m.group(1)
+            assert int(re.search(r"\.vgpr_spill_count:\s+(\d+)", b).group(1)) <= 4, m.group(1)
