@@ -373,8 +373,8 @@ constexpr float P_SUM_MAX = 1073741824.0f;   // 2^30
 // ---------------------------------------------------------------------------------------------
 // attn_h_kernel: blocks of 128 tokens, walked in half blocks of 64 keys.
 //
-// The matrix cores and the vector ALUs of a SIMD only overlap across wavefronts, so occupancy is
-// what keeps the MFMA pipe fed while other waves do their softmax.  A step over 64 keys needs half
+// A wavefront does its softmax between its two runs of MFMAs, so it is the other wavefronts of the
+// SIMD that keep the MFMA pipe fed meanwhile: occupancy matters.  A step over 64 keys needs half
 // the S and P registers and half the LDS of a step over 128, which lets three workgroups (twelve
 // wavefronts) live on a CU instead of two; everything else is attn_kernel: 4 waves x 32 query
 // rows, transposed products, K and V^T fragments straight from the packed tiles, DMA to LDS.
@@ -665,7 +665,8 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
   const int row_e = 32 * wave + ql_e;
   const size_t qrow_e = (size_t)bh * n_pad + (size_t)i * BLK + row_e;
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  const bool row_ok = row_e < blk_valid[i] && l_tot > 0.f;
+  const int rows_valid = BLK - (i == M_v - 1 ? pad_v : (i == M - 1 ? pad_c : 0));   // = blk_valid[i], without the load
+  const bool row_ok = row_e < rows_valid && l_tot > 0.f;
   const float inv = row_ok ? 1.0f / l_tot : 0.f;
   // natural-log sum of exp(logit) over the visited keys: the running maximum is in base-2 units
   if (lse != nullptr && hl_e == 0)
