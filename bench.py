@@ -186,6 +186,40 @@ def sustained_mfma_tflops(dev, seconds=0.15):
     return rate
 
 
+def valu_under_mfma(dev):
+    """ns per MFMA and SIMD of a loop of MFMAs with a fixed group of vector ALU instructions after each of them,
+    at one to four wavefronts per SIMD (bench_mfma_probe.so: bench_valu_under_mfma)."""
+    import ctypes
+    import torch
+    lib_path = os.path.join(ROOT, "bench_mfma_probe.so")
+    if not os.path.exists(lib_path):
+        sys.exit("bench.py: bench_mfma_probe.so is not built")
+    probe = ctypes.CDLL(lib_path).bench_valu_under_mfma
+    probe.argtypes = [ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    probe.restype = ctypes.c_int
+    kinds = ["mfma only", "attention step per mfma: exp, fma, add, half a bf16 pack", "the same plus half a v_max3",
+             "4 v_add_f32 per mfma", "5 v_add_f32 per mfma", "6 v_add_f32 per mfma"]
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    stream = torch.cuda.current_stream().cuda_stream
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    iters = 40000
+    table = {}
+    for kind, name in enumerate(kinds):
+        row = {}
+        for waves in (1, 2, 4):                 # one workgroup of four wavefronts per CU and per wave of a SIMD
+            n_wg = n_cu * waves
+            sink = torch.empty(n_wg * 256, device=dev, dtype=torch.float32)
+            for timed in (False, True):
+                a.record()
+                if probe(kind, sink.data_ptr(), sink.numel(), iters if timed else 2000, n_wg, stream) != 0:
+                    sys.exit("bench.py: bench_valu_under_mfma failed")
+                b.record()
+                torch.cuda.synchronize()
+            row["%d_waves_per_simd" % waves] = round(a.elapsed_time(b) * 1e6 / (iters * 4 * waves), 2)
+        table[name] = row
+    return {"unit": "ns per MFMA and SIMD", "mfma": "v_mfma_f32_32x32x16_bf16", "iters": iters, "table": table}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -201,11 +235,19 @@ def main():
     ap.add_argument("--zero-operands", action="store_true",
                     help="attribution run: the lists are selected on the real inputs, then Q, K, V are zeroed before "
                          "the attention is timed (same work, no data-dependent switching power)")
+    ap.add_argument("--valu-under-mfma", action="store_true",
+                    help="microbenchmark only: how many vector ALU instructions fit beside an MFMA on this part "
+                         "(prints its own JSON line and exits)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU; run with --gpus 1 (no multi-GPU path exists)")
 
     import torch
+    if args.valu_under_mfma:
+        if not torch.cuda.is_available():
+            sys.exit("bench.py: needs a GPU")
+        print(json.dumps({"microbenchmark": "valu_under_mfma", **valu_under_mfma("cuda:0")}))
+        return
     import jenga_inputs as ji
     from paper_2505_16864_amd import binding as B
     from paper_2505_16864_amd.layer import CarveLayer

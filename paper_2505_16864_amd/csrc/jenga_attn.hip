@@ -359,10 +359,10 @@ __device__ inline float max_with_other_half(float x) {
 }
 
 // attn_h_kernel takes the lazy reference one step further and drops the row maximum from the common
-// path.  The vector ALU port is shared with the issue of the MFMAs; measured, the exponentials, their
-// FMAs, the row sums and the bf16 packing of a step just fit beside its 32 MFMAs, and the 16 v_max3
-// with what follows them do not.  So a step forms its probabilities against the reference as it
-// stands and only looks at the sum: while a lane's 32 probabilities add up to at most P_SUM_MAX they
+// path: the maximum over the 32 logits of a lane (16 v_max3, a cross-half exchange, a compare) is a
+// chain that has to finish after the last MFMA of S and before the first exponential can issue, in
+// every step of every wavefront.  Without it a step forms its probabilities against the reference as
+// it stands and only looks at the sum: while a lane's 32 probabilities add up to at most P_SUM_MAX they
 // are all representable, and so are the float32 sums and products built from them (bf16 and float32
 // share the exponent range; 2^30 times the row length times |V| stays far below 2^127).  A sum above
 // the bound, infinite or undefined sends the step down the exact path: logits again (the K half is

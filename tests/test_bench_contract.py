@@ -20,3 +20,15 @@ def test_product_path_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text, f
+
+
+def test_measurement_aid_library_exports_both_probes():
+    # bench_mfma_probe.so is built next to bench.py by build(); bench.py loads it with ctypes
+    import ctypes
+    path = os.path.join(ROOT, "bench_mfma_probe.so")
+    if not os.path.exists(path):
+        import pytest
+        pytest.skip("bench_mfma_probe.so not built")
+    lib = ctypes.CDLL(path)
+    for name in ("bench_mfma_probe", "bench_valu_under_mfma"):
+        assert hasattr(lib, name), name
