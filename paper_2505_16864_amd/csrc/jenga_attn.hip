@@ -577,10 +577,6 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
       }
       return rs0 + rs1;
     };
-    // Common path: probabilities against the reference as it stands, no row maximum (see P_SUM_MAX).  Exact
-    // path: the logits again, the reference moved to the row maximum (the rescaling step of Alg. 4), and
-    // probabilities <= 1 in place of the first attempt.  Each branch forms and consumes its own S, so S never
-    // occupies registers beside a finished P.
     // the block of the next step, looked up under the arithmetic of this one
     auto advance = [&]() {
       if constexpr (PACED) {
@@ -595,6 +591,10 @@ __global__ __launch_bounds__(256, 3) void attn_h_kernel(
         j_next = min(max(idx[min(st + 1, steps - 1) >> 1], 0), M - 1);   // used after the next barrier
       }
     };
+    // Common path: probabilities against the reference as it stands, no row maximum (see P_SUM_MAX).  Exact
+    // path: the logits again, the reference moved to the row maximum (the rescaling step of Alg. 4), and
+    // probabilities <= 1 in place of the first attempt.  Each branch forms and consumes its own S, so S never
+    // occupies registers beside a finished P.
     float rs = 0.f;
     bool in_range = false;
     const bool first = unset;
