@@ -42,6 +42,9 @@ WORKLOADS = {
     # the headline layer with the time-paced walk of the attention kernel (flag bit 3 of the library)
     "hy720p_paced": dict(T=33, H=45, W=80, n_text=256, batch=1, heads=24, head_dim=128, block=128, topk=0.30, p=0.3,
                          flags=15),
+    # the p = 0.9 lists (long, of very uneven length) with the time-paced walk
+    "wan13b_paced": dict(T=20, H=30, W=52, n_text=512, batch=1, heads=12, head_dim=128, block=128, topk=0.30, p=0.9,
+                         flags=15),
     # the largest block count the library takes (M = 2048): 2032 vision blocks of 32 tokens + 16 text blocks
     "max_blocks": {"T": 8, "H": 64, "W": 127, "n_text": 512, "batch": 1, "heads": 2, "head_dim": 64, "block": 32,
                    "topk": 0.05, "p": 0.3},

@@ -87,7 +87,7 @@ def _boundary_blocks(lay):
 
 # (workload, seed, heads compared whole)
 SIZES = [("wan480p", 3000, (0, 19, 39)), ("hy_lowres", 4000, (0, 11, 23)), ("hy_lowres_amp", 4000, (0, 12, 23)),
-         ("wan13b", 3300, (0, 5, 11)), ("hy720p", 5000, (0, 23)), ("hy720p_paced", 5000, (11,)), ("hy720p_k10", 5000, ()), ("hy720p_k20", 5000, ()),
+         ("wan13b", 3300, (0, 5, 11)), ("wan13b_paced", 3300, (7,)), ("hy720p", 5000, (0, 23)), ("hy720p_paced", 5000, (11,)), ("hy720p_k10", 5000, ()), ("hy720p_k20", 5000, ()),
          ("wan480p_p90", 3100, (7,)), ("max_blocks", 6000, (0, 1))]
 
 
